@@ -1,0 +1,165 @@
+/*
+ * CPU oracle for the in-memory checkpointing hot path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, obviously-correct statement of what the GPU library must produce.  It is
+ * linked by nothing in the product: only the tests, the smoke check and the bench's CPU-baseline
+ * leg may load it.  It shares no code, header, table or helper with the HIP path.
+ *
+ * What it states (all on raw bytes; floating-point values are never interpreted):
+ *
+ *   stream   A rank's snapshot is its state tensors laid end to end as one flat vector, in the
+ *            caller's order, with no header and no padding (the flat "vectorized W" that
+ *            SplitParameter of Algorithm 1 cuts by index; section 1 says what a snapshot holds,
+ *            section 7.1 that it is lossless).
+ *   bucket   A bucket is a consecutive byte range of that flat vector; bucket b is stored at host
+ *            offset B_b, so the host copy equals the stream whatever the bucket lengths are
+ *            (generalises the two-way index cut of SplitParameter to many ranges).
+ *   parity   P = S_0 xor S_1 xor ... xor S_{k-1}, bit for bit (section 4.2, AEC encoding, Eq. 1;
+ *            section 6: erasure coding is bitwise XOR on the parameters' bit patterns).
+ *   decode   S_j = P xor (xor of all S_s, s != j)   (section 4.2, AEC decoding, Eq. 2).
+ *   load     The inverse slicing of the stream back into the tensors (section 4.3, step 1).
+ *
+ * Every loop is over single bytes.  The only concession to speed is an optional OpenMP split of
+ * the outer byte range (oracle_set_threads); the arithmetic per byte is unchanged.
+ *
+ * Return value of every function: 0 on success, -1 on an invalid argument.
+ */
+#include <stddef.h>
+#include <stdint.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static int g_threads = 1;
+
+void oracle_set_threads(int n) { g_threads = n < 1 ? 1 : n; }
+
+int oracle_get_threads(void) { return g_threads; }
+
+int oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Sum of the span sizes = length L of the stream. */
+uint64_t oracle_stream_bytes(const uint64_t *span_nbytes, uint64_t T)
+{
+    uint64_t L = 0;
+    for (uint64_t t = 0; t < T; ++t) L += span_nbytes[t];
+    return L;
+}
+
+/* stream = span_0 || span_1 || ... || span_{T-1}.  Zero-length spans contribute nothing. */
+int oracle_pack(const uint8_t *const *spans, const uint64_t *span_nbytes, uint64_t T,
+                uint8_t *stream, uint64_t stream_cap)
+{
+    if (oracle_stream_bytes(span_nbytes, T) > stream_cap) return -1;
+    uint64_t o = 0;
+    for (uint64_t t = 0; t < T; ++t) {
+        const uint8_t *src = spans[t];
+        const uint64_t n = span_nbytes[t];
+#pragma omp parallel for num_threads(g_threads) schedule(static) if (n > (1u << 20))
+        for (uint64_t i = 0; i < n; ++i) stream[o + i] = src[i];
+        o += n;
+    }
+    return 0;
+}
+
+/*
+ * The bucketed snapshot, step by step: for each bucket b in turn, for each stream offset o in
+ * [B_b, B_{b+1}), find the span that owns offset o and copy that one byte to host[o].
+ * Buckets must have positive length and together cover exactly [0, L).
+ */
+int oracle_pack_bucketed(const uint8_t *const *spans, const uint64_t *span_nbytes, uint64_t T,
+                         const uint64_t *bucket_nbytes, uint64_t NB,
+                         uint8_t *host, uint64_t host_cap)
+{
+    const uint64_t L = oracle_stream_bytes(span_nbytes, T);
+    if (L > host_cap) return -1;
+    uint64_t covered = 0;
+    for (uint64_t b = 0; b < NB; ++b) {
+        if (bucket_nbytes[b] == 0) return -1;
+        covered += bucket_nbytes[b];
+    }
+    if (covered != L) return -1;
+
+    uint64_t B = 0;                 /* start of the current bucket in the stream */
+    for (uint64_t b = 0; b < NB; ++b) {
+        const uint64_t E = B + bucket_nbytes[b];
+        /* locate the span that owns offset B */
+        uint64_t t = 0, span_start = 0;
+        while (t < T && span_start + span_nbytes[t] <= B) { span_start += span_nbytes[t]; ++t; }
+        for (uint64_t o = B; o < E; ++o) {
+            while (o >= span_start + span_nbytes[t]) { span_start += span_nbytes[t]; ++t; }
+            host[o] = spans[t][o - span_start];
+        }
+        B = E;
+    }
+    return 0;
+}
+
+/* Inverse of oracle_pack: span_t = stream[off_t : off_t + nbytes_t]. */
+int oracle_unpack(const uint8_t *stream, uint64_t stream_bytes,
+                  const uint64_t *span_nbytes, uint64_t T, uint8_t *const *spans_out)
+{
+    if (oracle_stream_bytes(span_nbytes, T) != stream_bytes) return -1;
+    uint64_t o = 0;
+    for (uint64_t t = 0; t < T; ++t) {
+        uint8_t *dst = spans_out[t];
+        const uint64_t n = span_nbytes[t];
+#pragma omp parallel for num_threads(g_threads) schedule(static) if (n > (1u << 20))
+        for (uint64_t i = 0; i < n; ++i) dst[i] = stream[o + i];
+        o += n;
+    }
+    return 0;
+}
+
+/* parity[i] = shards[0][i] ^ ... ^ shards[k-1][i], i in [0, L).  k >= 1. */
+int oracle_encode(const uint8_t *const *shards, uint32_t k, uint64_t L, uint8_t *parity)
+{
+    if (k < 1) return -1;
+#pragma omp parallel for num_threads(g_threads) schedule(static) if (L > (1u << 20))
+    for (uint64_t i = 0; i < L; ++i) {
+        uint8_t p = 0;
+        for (uint32_t s = 0; s < k; ++s) p ^= shards[s][i];
+        parity[i] = p;
+    }
+    return 0;
+}
+
+/*
+ * Shards of unequal length: each is taken as zero-extended to Lmax = max length (0 is the
+ * identity of XOR).  Not reachable through the GPU library (it rejects unequal lengths); kept to
+ * state the reading and for a unit test.
+ */
+int oracle_encode_padded(const uint8_t *const *shards, const uint64_t *lens, uint32_t k,
+                         uint8_t *parity, uint64_t parity_cap)
+{
+    if (k < 1) return -1;
+    uint64_t Lmax = 0;
+    for (uint32_t s = 0; s < k; ++s) if (lens[s] > Lmax) Lmax = lens[s];
+    if (Lmax > parity_cap) return -1;
+    for (uint64_t i = 0; i < Lmax; ++i) {
+        uint8_t p = 0;
+        for (uint32_t s = 0; s < k; ++s) p ^= (i < lens[s]) ? shards[s][i] : 0;
+        parity[i] = p;
+    }
+    return 0;
+}
+
+/* out[i] = parity[i] ^ survivors[0][i] ^ ... ^ survivors[n-1][i]; n = k-1 may be 0. */
+int oracle_reconstruct(const uint8_t *const *survivors, uint32_t n_survivors,
+                       const uint8_t *parity, uint64_t L, uint8_t *out)
+{
+#pragma omp parallel for num_threads(g_threads) schedule(static) if (L > (1u << 20))
+    for (uint64_t i = 0; i < L; ++i) {
+        uint8_t v = parity[i];
+        for (uint32_t s = 0; s < n_survivors; ++s) v ^= survivors[s][i];
+        out[i] = v;
+    }
+    return 0;
+}

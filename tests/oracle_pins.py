@@ -1,0 +1,261 @@
+"""Pins for the CPU oracle: checks that do not come from the oracle itself.
+
+Each ``pin_*`` function takes an oracle object (``oracle.Oracle``) and raises AssertionError when
+the oracle disagrees with what the paper and the mathematics fix: hand-worked fixtures under
+``tests/golden/``, closed forms, invariants (zero-sum, round trip, bucket independence,
+linearity), special cases that reduce to a library routine (memcpy-like copy, ``numpy.bitwise_xor``)
+and brute force in pure Python on tiny inputs.  ``test_oracle_pins.py`` runs them on the real
+oracle; ``test_oracle_mutants.py`` runs them on builds with a planted mistake and expects a failure.
+"""
+from __future__ import annotations
+
+import os
+
+import numpy as np
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _read_golden(name):
+    rows = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, _, rest = line.partition(":")
+            rows.append((key.strip(), rest.split()))
+    return rows
+
+
+def _hex(tokens):
+    return np.array([int(t, 16) for t in tokens], dtype=np.uint8)
+
+
+def _rand(rng, n):
+    return rng.integers(0, 256, size=int(n), dtype=np.uint8)
+
+
+# ------------------------------------------------------------------------------------------------
+# golden fixtures (hand-worked)
+# ------------------------------------------------------------------------------------------------
+def pin_golden_xor(orc):
+    """Section 4.2 Eq. 1 / Eq. 2 on the hand-worked bytes."""
+    for name in ("xor_parity_worked.txt", "float_bits_worked.txt"):
+        rows = _read_golden(name)
+        shards = [_hex(t) for k, t in rows if k == "shard"]
+        parity = [_hex(t) for k, t in rows if k == "parity"][0]
+        assert np.array_equal(orc.encode(shards), parity), name
+        for j in range(len(shards)):
+            surv = [s for i, s in enumerate(shards) if i != j]
+            assert np.array_equal(orc.reconstruct(surv, parity), shards[j]), (name, j)
+
+
+def pin_golden_pack(orc):
+    """Flat-vector layout (Algorithm 1, SplitParameter) on the hand-written bytes."""
+    rows = _read_golden("pack_worked.txt")
+    spans = [_hex(t) for k, t in rows if k == "span"]
+    stream = [_hex(t) for k, t in rows if k == "stream"][0]
+    assert np.array_equal(orc.pack(spans), stream)
+    for k, t in rows:
+        if k == "buckets":
+            b = [int(x) for x in t]
+            assert np.array_equal(orc.pack_bucketed(spans, b), stream), b
+    outs = orc.unpack(stream, [s.size for s in spans])
+    for a, b in zip(outs, spans):
+        assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------------------------------------
+# closed forms
+# ------------------------------------------------------------------------------------------------
+def pin_closed_form_parity(orc):
+    L = 1000
+    i = np.arange(L, dtype=np.uint64)
+    # one distinct bit per shard: the parity has exactly the k low bits set
+    for k in (1, 2, 3, 5, 8):
+        shards = [np.full(L, 1 << s, dtype=np.uint8) for s in range(k)]
+        assert np.all(orc.encode(shards) == (1 << k) - 1), k
+    # k copies of the ramp i mod 256: zero for even k, the ramp for odd k
+    ramp = (i % 256).astype(np.uint8)
+    for k in (2, 3, 4, 7, 8):
+        p = orc.encode([ramp.copy() for _ in range(k)])
+        assert np.array_equal(p, ramp if k % 2 else np.zeros(L, np.uint8)), k
+    # shard s = (i >> s) & 1 for s < 8: parity byte = popcount(i & 0xff) mod 2
+    shards = [((i >> s) & 1).astype(np.uint8) for s in range(8)]
+    pop = np.array([bin(int(x) & 0xFF).count("1") & 1 for x in i], dtype=np.uint8)
+    assert np.array_equal(orc.encode(shards), pop)
+
+
+def pin_closed_form_pack(orc):
+    """Span t filled with byte value t: stream[o] is the index of the span owning offset o."""
+    rng = np.random.default_rng(7)
+    sizes = [int(x) for x in rng.integers(0, 300, size=40)]
+    sizes[5] = 0
+    sizes[6] = 0
+    spans = [np.full(n, t, dtype=np.uint8) for t, n in enumerate(sizes)]
+    ends = np.cumsum(sizes)
+    L = int(ends[-1])
+    owner = np.searchsorted(ends, np.arange(L), side="right").astype(np.uint8)
+    assert np.array_equal(orc.pack(spans), owner)
+    assert np.array_equal(orc.pack_bucketed(spans, [L]), owner)
+    assert np.array_equal(orc.pack_bucketed(spans, [1] * L), owner)
+
+
+# ------------------------------------------------------------------------------------------------
+# invariants
+# ------------------------------------------------------------------------------------------------
+def pin_zero_sum(orc):
+    """XOR of all shards and the parity is zero (follows from Eq. 1)."""
+    rng = np.random.default_rng(11)
+    for k in (2, 3, 4, 8, 9):
+        for L in (0, 1, 15, 16, 17, 255, 4099, 70001):
+            shards = [_rand(rng, L) for _ in range(k)]
+            p = orc.encode(shards)
+            assert p.size == L                      # parity volume = one protected unit
+            acc = np.bitwise_xor.reduce(np.stack(shards + [p]), axis=0) if L else p
+            assert not acc.any(), (k, L)
+
+
+def pin_round_trip_and_bucket_independence(orc):
+    """unpack(pack(x)) == x for any bucket list; the host copy does not depend on the buckets."""
+    rng = np.random.default_rng(13)
+    sizes = [0, 1, 2, 3, 5, 16, 17, 31, 0, 64, 255, 256, 1000, 4097, 7, 0, 33]
+    spans = [_rand(rng, n) for n in sizes]
+    L = sum(sizes)
+    ref = np.concatenate(spans)                      # library statement of "end to end"
+    assert np.array_equal(orc.pack(spans), ref)
+    bucket_lists = [[L], [1] * L, [16] * (L // 16) + ([L % 16] if L % 16 else []),
+                    [4096] * (L // 4096) + ([L % 4096] if L % 4096 else [])]
+    for _ in range(4):
+        b, left = [], L
+        while left:
+            n = min(left, 2 * int(rng.integers(1, 400)) + 1)
+            b.append(n)
+            left -= n
+        bucket_lists.append(b)
+    for b in bucket_lists:
+        host = np.full(L + 64, 0xA5, dtype=np.uint8)          # guard band after the stream
+        orc.pack_bucketed(spans, b, host)
+        assert np.array_equal(host[:L], ref), b[:4]
+        assert np.all(host[L:] == 0xA5)                        # never writes past L
+        outs = orc.unpack(host[:L].copy(), sizes)
+        for a, s in zip(outs, spans):
+            assert np.array_equal(a, s)
+
+
+def pin_bruteforce_reconstruct(orc):
+    """Every-j reconstruct against a pure-Python triple loop on tiny inputs (Eq. 2)."""
+    rng = np.random.default_rng(17)
+    for k in (2, 3, 4, 8):
+        for L in (0, 1, 15, 16, 17, 255, 1031):
+            shards = [_rand(rng, L) for _ in range(k)]
+            lists = [s.tolist() for s in shards]
+            # brute-force parity: bit by bit, counting ones modulo 2
+            par = []
+            for i in range(L):
+                byte = 0
+                for bit in range(8):
+                    ones = 0
+                    for s in range(k):
+                        ones += (lists[s][i] >> bit) & 1
+                    byte |= (ones & 1) << bit
+                par.append(byte)
+            par = np.array(par, dtype=np.uint8)
+            assert np.array_equal(orc.encode(shards), par), (k, L)
+            for j in range(k):
+                surv = [shards[s] for s in range(k) if s != j]
+                assert np.array_equal(orc.reconstruct(surv, par), shards[j]), (k, L, j)
+
+
+def pin_special_cases(orc):
+    rng = np.random.default_rng(19)
+    a, b, c = (_rand(rng, 5003) for _ in range(3))
+    # one span: pack is a plain copy
+    assert np.array_equal(orc.pack([a]), a)
+    assert np.array_equal(orc.pack_bucketed([a], [5003]), a)
+    # k = 1: the parity of a single shard is the shard; reconstruct with no survivors is the parity
+    assert np.array_equal(orc.encode([a]), a)
+    assert np.array_equal(orc.reconstruct([], a), a)
+    # k = 2: numpy.bitwise_xor
+    assert np.array_equal(orc.encode([a, b]), np.bitwise_xor(a, b))
+    assert np.array_equal(orc.reconstruct([a], np.bitwise_xor(a, b)), b)
+    # two identical shards cancel; an all-zero shard changes nothing
+    assert not orc.encode([a, a.copy()]).any()
+    z = np.zeros_like(a)
+    assert np.array_equal(orc.encode([a, z, b, c]), orc.encode([a, b, c]))
+    # order of the shards does not matter
+    assert np.array_equal(orc.encode([a, b, c]), orc.encode([c, a, b]))
+    # reconstruct uses every survivor: k = 3
+    p = np.bitwise_xor(np.bitwise_xor(a, b), c)
+    assert np.array_equal(orc.reconstruct([a, c], p), b)
+
+
+def pin_linearity_and_word_width(orc):
+    rng = np.random.default_rng(23)
+    k, L = 5, 4096
+    shards = [_rand(rng, L) for _ in range(k)]
+    p0 = orc.encode(shards)
+    # flipping one bit of one shard flips exactly that bit of the parity
+    for (s, i, bit) in ((0, 0, 0), (2, 17, 7), (4, L - 1, 3), (1, 2048, 5)):
+        mod = [x.copy() for x in shards]
+        mod[s][i] ^= np.uint8(1 << bit)
+        diff = np.bitwise_xor(orc.encode(mod), p0)
+        assert diff[i] == (1 << bit) and np.count_nonzero(diff) == 1
+    # the same parity when the shards are XORed as 16-, 32- or 64-bit words
+    for dt in (np.uint16, np.uint32, np.uint64):
+        acc = np.zeros(L // np.dtype(dt).itemsize, dtype=dt)
+        for s in shards:
+            acc ^= s.view(dt)
+        assert np.array_equal(acc.view(np.uint8), p0), dt
+
+
+def pin_float_payloads(orc):
+    """NaN payloads, infinities, signed zeros and denormals go through as bits."""
+    pats = np.array([0x7FC00123, 0xFFC0FFEE, 0x7F800000, 0xFF800000, 0x80000000, 0x00000001,
+                     0x807FFFFF, 0x7F800001], dtype=np.uint32)
+    a = pats.view(np.uint8).copy()
+    b = np.roll(pats, 3).view(np.uint8).copy()
+    c = np.roll(pats, 5).view(np.uint8).copy()
+    p = orc.encode([a, b, c])
+    assert np.array_equal(p.view(np.uint32), pats ^ np.roll(pats, 3) ^ np.roll(pats, 5))
+    assert np.array_equal(orc.reconstruct([a, c], p).view(np.uint32), np.roll(pats, 3))
+    h = np.array([0x7FC1, 0xFF80, 0x8000, 0x0001], dtype=np.uint16).view(np.uint8).copy()
+    s = orc.pack([a, h, b])
+    assert np.array_equal(s[a.size:a.size + h.size].view(np.uint16),
+                          np.array([0x7FC1, 0xFF80, 0x8000, 0x0001], dtype=np.uint16))
+
+
+def pin_padded(orc):
+    """Unequal lengths: identical to the equal-length code on explicitly zero-extended shards."""
+    rng = np.random.default_rng(29)
+    lens = [100, 37, 0, 250, 249]
+    shards = [_rand(rng, n) for n in lens]
+    Lmax = max(lens)
+    ext = [np.concatenate([s, np.zeros(Lmax - s.size, np.uint8)]) for s in shards]
+    want = np.bitwise_xor.reduce(np.stack(ext), axis=0)
+    assert np.array_equal(orc.encode_padded(shards), want)
+    # beyond every other shard's end the parity is the longest shard itself
+    assert np.array_equal(want[249:], shards[3][249:])
+
+
+def pin_rejects(orc):
+    a = np.arange(10, dtype=np.uint8)
+    for bad in ([0, 10], [4, 5], [4, 7], []):
+        try:
+            orc.pack_bucketed([a], bad)
+        except ValueError:
+            continue
+        raise AssertionError(f"bucket list {bad} accepted")
+    try:
+        orc.unpack(a, [3, 3])
+    except ValueError:
+        pass
+    else:
+        raise AssertionError("unpack accepted sizes that do not sum to the stream length")
+
+
+ALL_PINS = [pin_golden_xor, pin_golden_pack, pin_closed_form_parity, pin_closed_form_pack,
+            pin_zero_sum, pin_round_trip_and_bucket_independence, pin_bruteforce_reconstruct,
+            pin_special_cases, pin_linearity_and_word_width, pin_float_payloads, pin_padded,
+            pin_rejects]
