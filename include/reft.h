@@ -1,0 +1,188 @@
+/*
+ * reft.h - C ABI of libreft: the device-side hot path of in-memory checkpointing for one rank.
+ *
+ * What the library does, in the paper's terms (REFT, arXiv 2310.12670):
+ *   - snapshot: the rank's state tensors (parameters and optimizer states, section 1) are taken
+ *     as one flat vector, the "vectorized W" that SplitParameter of Algorithm 1 cuts by index;
+ *     consecutive byte ranges of it ("buckets") are gathered on the GPU and copied to a pinned
+ *     host buffer asynchronously to training (section 4.1; section 6: pinned host buffers);
+ *   - protect: the k snapshot shards of a node are encoded into one XOR parity unit on the
+ *     device (section 4.2, Asynchronous Erasure Coding, Eq. 1; section 6: bitwise XOR);
+ *   - load: a shard is copied back from host memory into the tensors (section 4.3, step 1) and a
+ *     single lost shard is decoded from the parity and the survivors (section 4.2, Eq. 2;
+ *     section 4.3, step 3).
+ *
+ * Vocabulary
+ *   span    one tensor's raw bytes: a device pointer and a byte count (may be 0).
+ *   stream  the tight concatenation of a shard's spans in list order, L bytes; no header, no
+ *           padding.  All results are defined on the stream's bytes; values are never interpreted.
+ *   bucket  a consecutive byte range [B_b, B_{b+1}) of the stream; a transport unit only: the
+ *           host copy produced by reft_snapshot_pack equals the stream whatever the buckets are.
+ *   plan    the sizes of the spans and buckets of a shard (no pointers, no data); k shards that
+ *           are protected together share one plan (identical span sizes).
+ *
+ * General rules
+ *   - Every function returns 0 (REFT_OK) or a negative REFT_E* code; it never throws or aborts.
+ *     reft_last_error() gives a message for the calling thread's most recent failure.
+ *   - "device" pointers are HIP device addresses on the plan's GPU; "host" pointers are host
+ *     addresses.  Pointer *arrays* (span_ptrs, shards) are host arrays holding device addresses.
+ *   - The caller owns all data buffers, the staging ring, the pinned host buffer and the HIP
+ *     streams.  The library owns only the plan (host tables, their device copies, events).
+ *   - The data-moving calls enqueue work on the given streams and return; results are complete
+ *     when those streams (or reft_snapshot_wait / reft_restore_wait) have been synchronised.
+ *     Source data must not be modified, and pointer arrays' targets not freed, before that.
+ *     The pointer arrays themselves are copied before the call returns.
+ *   - A plan is bound to the GPU that was current at reft_plan_create; calls on one plan must not
+ *     be issued from two host threads at once.  Streams stay at the default priority.
+ *   - reft_stream is a hipStream_t passed as void* (NULL = the default stream).
+ */
+#ifndef REFT_H
+#define REFT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define REFT_OK               0
+#define REFT_EINVAL         (-1)  /* null pointer, k out of range, T == 0, zero-length bucket     */
+#define REFT_ESIZE          (-2)  /* a buffer is too small or a length does not match the plan    */
+#define REFT_EHIP           (-3)  /* a HIP runtime call failed; text in reft_last_error()         */
+#define REFT_EUNRECOVERABLE (-4)  /* more than one shard lost: beyond what one parity can decode  */
+
+#define REFT_MAX_K 32             /* most shards (or survivors + parity) in one call              */
+
+typedef struct reft_plan reft_plan;
+typedef void *reft_stream;
+
+/* ---- S0: plan (host integer arithmetic; done once and reused for every snapshot) -------------
+ * The sizing and splitting that Algorithm 1 performs on the host per stage: prefix sums of the
+ * span sizes, the bucket boundaries, and the tile table the kernels walk.
+ *
+ * span_nbytes[T]    host array, byte size of each span in stream order (zeros allowed), T >= 1.
+ * uniform_bucket    if non-zero: buckets of this many bytes (the last one shorter);
+ *                   bucket_nbytes/NB are ignored.
+ * bucket_nbytes[NB] otherwise: host array of positive bucket lengths whose sum must equal L
+ *                   (NB may be 0 only when L == 0).  With bucket_nbytes == NULL, NB == 0 and
+ *                   uniform_bucket == 0 the whole stream is one bucket.
+ * out               receives the plan; destroy it with reft_plan_destroy.
+ * Allocates the plan's device tables and events on the current GPU (the only allocating call).
+ * Errors: REFT_EINVAL (null out/span_nbytes, T == 0, a zero-length bucket), REFT_ESIZE (bucket
+ * lengths do not sum to L), REFT_EHIP.
+ */
+int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
+                     const uint64_t *bucket_nbytes, uint64_t NB, uint64_t uniform_bucket,
+                     reft_plan **out);
+void reft_plan_destroy(reft_plan *plan);                 /* NULL is allowed                       */
+uint64_t reft_plan_stream_bytes(const reft_plan *plan);  /* L                                     */
+uint64_t reft_plan_num_spans(const reft_plan *plan);     /* T                                     */
+uint64_t reft_plan_num_buckets(const reft_plan *plan);   /* NB                                    */
+uint64_t reft_plan_max_bucket_bytes(const reft_plan *plan);
+/* Smallest staging ring (bytes) that holds one bucket; n slots need n times this. */
+uint64_t reft_plan_staging_slot_bytes(const reft_plan *plan);
+/* Byte range [*begin, *end) of bucket b.  REFT_EINVAL if b >= NB. */
+int reft_plan_bucket_range(const reft_plan *plan, uint64_t b, uint64_t *begin, uint64_t *end);
+/* Stream offset at which span t starts (t == T gives L).  REFT_EINVAL if t > T. */
+int reft_plan_span_offset(const reft_plan *plan, uint64_t t, uint64_t *offset);
+/* The kernels' work decomposition: tiles of *tile_bytes consecutive stream bytes, *ntiles of them;
+ * reft_plan_tile_first_span gives the first span owning a byte of tile t (for inspection/tests). */
+int reft_plan_tile_info(const reft_plan *plan, uint64_t *tile_bytes, uint64_t *ntiles);
+int reft_plan_tile_first_span(const reft_plan *plan, uint64_t t, uint64_t *span);
+/* The index cut of SplitParameter (Algorithm 1): floor(n * t_bubble / t_ss) with n = L bytes,
+ * clamped to [0, L]; t_ss must be > 0.  Returns the cut through *cut. */
+int reft_plan_split(const reft_plan *plan, double t_bubble, double t_ss, uint64_t *cut);
+
+/* ---- S1 + S2 + S3: bucketed snapshot of one shard into pinned host memory -----------------------
+ * For each bucket in order: a gather kernel on pack_stream copies the bucket's bytes from the
+ * ragged span tensors into a slot of the staging ring; a hipMemcpyAsync on copy_stream moves the
+ * slot to host_dst + B_b.  Events order slot reuse; with >= 2 slots gather and copy overlap.
+ * After the last copy a completion event is recorded (see reft_snapshot_wait): the snapshot is
+ * complete only when every bucket has landed (section 4.4: COMPLETED when all tensors are
+ * snapshotted).  Postcondition: host_dst[0..L) == stream; host_dst[L..) untouched.
+ *
+ * span_ptrs[T]   host array of device pointers (may be NULL where the span has 0 bytes).
+ * staging        device buffer of staging_bytes >= reft_plan_staging_slot_bytes(plan); up to 4
+ *                slots are used.  Its contents are scratch.
+ * host_dst       host buffer of host_cap >= L bytes; should be pinned (hipHostMalloc) for the
+ *                copy to be asynchronous and fast.
+ * Errors: REFT_EINVAL, REFT_ESIZE (host_cap < L, staging smaller than one slot), REFT_EHIP.
+ */
+int reft_snapshot_pack(reft_plan *plan, const void *const *span_ptrs,
+                       void *staging, uint64_t staging_bytes,
+                       void *host_dst, uint64_t host_cap,
+                       reft_stream pack_stream, reft_stream copy_stream);
+/* Block until the most recent reft_snapshot_pack on this plan has fully landed on the host. */
+int reft_snapshot_wait(reft_plan *plan);
+/* 1 if it has landed (or none was issued), 0 if still in flight, negative on error. */
+int reft_snapshot_query(reft_plan *plan);
+
+/* ---- S1 alone / S7 alone: the gather and scatter kernels between device buffers ------------------
+ * reft_pack_device:   dst_dev[0..L) = stream of the spans           (one launch over [0, L)).
+ * reft_unpack_device: the spans = slices of src_dev[0..L)           (inverse of the above).
+ * dst_cap >= L and src_bytes == L are checked (REFT_ESIZE).
+ */
+int reft_pack_device(reft_plan *plan, const void *const *span_ptrs,
+                     void *dst_dev, uint64_t dst_cap, reft_stream stream);
+int reft_unpack_device(reft_plan *plan, const void *src_dev, uint64_t src_bytes,
+                       void *const *span_ptrs, reft_stream stream);
+
+/* ---- S4: XOR parity over the k shards of the node (section 4.2, Eq. 1) ---------------------------
+ * parity_dev[i] = S_0[i] ^ ... ^ S_{k-1}[i] for i in [0, L), where S_s is the stream of shard s
+ * read in place through its span pointers (no packed copy of the shards is needed).
+ *
+ * shard_span_ptrs  host array of k*T device pointers, row-major: entry s*T + t is span t of
+ *                  shard s.  A shard that is already packed is expressed with a 1-span plan.
+ * k                1 <= k <= REFT_MAX_K (k == 1 copies the stream).
+ * parity_dev       device buffer of at least L bytes; must not overlap any span.
+ * Errors: REFT_EINVAL (k out of range, null), REFT_EHIP.
+ */
+int reft_parity_encode(reft_plan *plan, const void *const *shard_span_ptrs, uint32_t k,
+                       void *parity_dev, reft_stream stream);
+
+/* ---- S6: decode the single lost shard (section 4.2, Eq. 2) ---------------------------------------
+ * out_dev[i] = parity[i] ^ (XOR over the surviving shards s of shards[s][i]), i in [0, L).
+ *
+ * shards[k]   host array of device pointers to the packed streams (L bytes each) of the node's k
+ *             shards; exactly one entry is NULL: the lost shard.
+ * parity      device pointer, L bytes.   out_dev: device buffer of L bytes, no overlap with inputs.
+ * lost_index  if not NULL, receives the index of the NULL entry.
+ * Errors: REFT_EUNRECOVERABLE if two or more entries are NULL (one parity tolerates one loss per
+ * group, section 4.2); REFT_EINVAL if none is NULL, k < 1 or k > REFT_MAX_K - 1, or a null
+ * parity/out with L > 0; REFT_EHIP.
+ */
+int reft_reconstruct(const void *const *shards, uint32_t k, const void *parity, uint64_t L,
+                     void *out_dev, uint32_t *lost_index, reft_stream stream);
+
+/* ---- S5 + S7: load a shard from pinned host memory back into its tensors (section 4.3, step 1) ---
+ * For each bucket: hipMemcpyAsync host_src + B_b -> staging slot on copy_stream, then a scatter
+ * kernel on unpack_stream writes the slot's bytes into the span tensors.
+ * host_bytes must equal L (REFT_ESIZE).  Other arguments as for reft_snapshot_pack.
+ */
+int reft_restore(reft_plan *plan, const void *host_src, uint64_t host_bytes,
+                 void *staging, uint64_t staging_bytes,
+                 void *const *span_ptrs, reft_stream copy_stream, reft_stream unpack_stream);
+int reft_restore_wait(reft_plan *plan);
+
+/* ---- tuning and diagnostics -----------------------------------------------------------------------
+ * Process-wide launch parameters, read at each launch:
+ *   "max_wgs"      cap on workgroups per kernel launch (0 = 8 per compute unit).  A small cap keeps
+ *                  a snapshot kernel on few compute units while training kernels run beside it.
+ *   "nontemporal"  1 = streaming (non-temporal) loads and stores in the kernels, 0 = plain.
+ *   "unroll"       16-byte chunks in flight per thread and source: 1, 2 or 4.
+ * Read when a plan is created:
+ *   "tile_shift"   log2 of the tile size in bytes, 12..24 (default 16 = 64 KiB).
+ *   "host_only_plans"  1 = reft_plan_create builds only the host-side sizing (no GPU needed);
+ *                  such a plan answers the reft_plan_* queries and is refused (REFT_EINVAL) by
+ *                  every call that would touch the GPU.
+ * reft_set_tunable returns REFT_EINVAL for an unknown name or a value out of range.
+ */
+int reft_set_tunable(const char *name, uint64_t value);
+int reft_get_tunable(const char *name, uint64_t *value);
+const char *reft_last_error(void);   /* thread-local, never NULL */
+const char *reft_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REFT_H */

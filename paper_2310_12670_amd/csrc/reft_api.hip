@@ -1,0 +1,649 @@
+// C-ABI host logic of libreft (see include/reft.h): the plan (host integer arithmetic and device
+// tables), the bucket pipelines that pair the gather / scatter kernels with chunked
+// hipMemcpyAsync transfers, and the XOR encode / decode entry points.
+#include "../../include/reft.h"
+#include "reft_internal.hpp"
+
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace reft;
+
+// ------------------------------------------------------------------------------------------------
+// errors and tunables
+// ------------------------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIPCHK(expr)                                                                              \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess)                                                                     \
+            return fail(REFT_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_),         \
+                        __FILE__, __LINE__);                                                      \
+    } while (0)
+
+static std::atomic<uint64_t> g_max_wgs{0};       // 0 = 8 per compute unit
+static std::atomic<uint64_t> g_nontemporal{1};
+static std::atomic<uint64_t> g_unroll{4};
+static std::atomic<uint64_t> g_tile_shift{16};   // read at plan creation
+static std::atomic<uint64_t> g_host_only{0};     // read at plan creation: no device tables
+
+extern "C" int reft_set_tunable(const char *name, uint64_t value)
+{
+    if (!name) return fail(REFT_EINVAL, "reft_set_tunable: null name");
+    if (!strcmp(name, "max_wgs")) {
+        if (value > (1u << 20)) return fail(REFT_EINVAL, "max_wgs out of range");
+        g_max_wgs = value;
+    } else if (!strcmp(name, "nontemporal")) {
+        if (value > 1) return fail(REFT_EINVAL, "nontemporal must be 0 or 1");
+        g_nontemporal = value;
+    } else if (!strcmp(name, "unroll")) {
+        if (value != 1 && value != 2 && value != 4)
+            return fail(REFT_EINVAL, "unroll must be 1, 2 or 4");
+        g_unroll = value;
+    } else if (!strcmp(name, "tile_shift")) {
+        if (value < 12 || value > 24) return fail(REFT_EINVAL, "tile_shift must be in [12, 24]");
+        g_tile_shift = value;
+    } else if (!strcmp(name, "host_only_plans")) {
+        if (value > 1) return fail(REFT_EINVAL, "host_only_plans must be 0 or 1");
+        g_host_only = value;
+    } else {
+        return fail(REFT_EINVAL, "unknown tunable '%s'", name);
+    }
+    return REFT_OK;
+}
+
+extern "C" int reft_get_tunable(const char *name, uint64_t *value)
+{
+    if (!name || !value) return fail(REFT_EINVAL, "reft_get_tunable: null argument");
+    if (!strcmp(name, "max_wgs")) *value = g_max_wgs;
+    else if (!strcmp(name, "nontemporal")) *value = g_nontemporal;
+    else if (!strcmp(name, "unroll")) *value = g_unroll;
+    else if (!strcmp(name, "tile_shift")) *value = g_tile_shift;
+    else if (!strcmp(name, "host_only_plans")) *value = g_host_only;
+    else return fail(REFT_EINVAL, "unknown tunable '%s'", name);
+    return REFT_OK;
+}
+
+extern "C" const char *reft_last_error(void) { return g_err; }
+extern "C" const char *reft_version(void) { return "libreft 0.1 (gfx950)"; }
+
+// ------------------------------------------------------------------------------------------------
+// plan
+// ------------------------------------------------------------------------------------------------
+namespace {
+constexpr int kRing = 4;        // pointer-table uploads that may be in flight at once
+constexpr int kMaxSlots = 4;    // staging slots used by the bucket pipelines
+
+struct Event {
+    hipEvent_t ev = nullptr;
+    bool recorded = false;
+};
+}  // namespace
+
+struct reft_plan {
+    bool host_only = false;           // sizing only: no device tables, data calls are refused
+    int device = 0;
+    int num_cus = 256;
+    uint64_t T = 0, NB = 0, L = 0, max_bucket = 0;
+    uint32_t tile_shift = 16;
+    uint64_t ntiles = 0;
+    std::vector<uint64_t> off;        // [T+1]
+    std::vector<uint64_t> bstart;     // [NB+1]
+    std::vector<uint32_t> first;      // [ntiles] host copy of the tile table
+    uint64_t *d_off = nullptr;
+    uint32_t *d_first = nullptr;
+    // ring of pointer tables: pinned host mirror and device copy, ring_rows rows of T per entry
+    uint32_t ring_rows = 0;
+    uint64_t *h_ptr = nullptr;
+    uint64_t *d_ptr = nullptr;
+    Event ring_ev[kRing];
+    unsigned ring_next = 0;
+    // bucket pipelines
+    Event pack_filled[kMaxSlots], pack_free[kMaxSlots], pack_done;
+    Event rest_filled[kMaxSlots], rest_free[kMaxSlots], rest_done;
+
+    PlanTables tables() const { return PlanTables{d_off, d_first, T, L, tile_shift}; }
+};
+
+static LaunchCfg launch_cfg(const reft_plan *p)
+{
+    uint64_t w = g_max_wgs;
+    if (w == 0) w = 8ull * (uint64_t)(p ? p->num_cus : 256);
+    return LaunchCfg{(uint32_t)w, (uint32_t)g_unroll.load(), g_nontemporal.load() != 0};
+}
+
+static int make_event(Event &e)
+{
+    HIPCHK(hipEventCreateWithFlags(&e.ev, hipEventDisableTiming));
+    e.recorded = false;
+    return REFT_OK;
+}
+
+static int record(Event &e, hipStream_t s)
+{
+    HIPCHK(hipEventRecord(e.ev, s));
+    e.recorded = true;
+    return REFT_OK;
+}
+
+static int wait_on(hipStream_t s, const Event &e)
+{
+    if (e.recorded) HIPCHK(hipStreamWaitEvent(s, e.ev, 0));
+    return REFT_OK;
+}
+
+static void free_ring(reft_plan *p)
+{
+    if (p->h_ptr) (void)hipHostFree(p->h_ptr);
+    if (p->d_ptr) (void)hipFree(p->d_ptr);
+    p->h_ptr = nullptr;
+    p->d_ptr = nullptr;
+    p->ring_rows = 0;
+}
+
+// Make room for pointer tables of `rows` rows.  Growing waits for earlier uploads to be consumed.
+static int ensure_ring(reft_plan *p, uint32_t rows)
+{
+    if (rows <= p->ring_rows) return REFT_OK;
+    for (int i = 0; i < kRing; ++i)
+        if (p->ring_ev[i].recorded) HIPCHK(hipEventSynchronize(p->ring_ev[i].ev));
+    free_ring(p);
+    const size_t bytes = (size_t)kRing * rows * p->T * sizeof(uint64_t);
+    HIPCHK(hipHostMalloc((void **)&p->h_ptr, bytes, hipHostMallocDefault));
+    HIPCHK(hipMalloc((void **)&p->d_ptr, bytes));
+    p->ring_rows = rows;
+    return REFT_OK;
+}
+
+// Copy `rows` x T pointers into the next ring entry and start its upload on `s`.
+// On success *dev_tab is the device table and *entry the ring index to release after the last
+// kernel that reads it.
+static int upload_ptrs(reft_plan *p, const void *const *ptrs, uint32_t rows, hipStream_t s,
+                       const uint64_t **dev_tab, int *entry)
+{
+    int rc = ensure_ring(p, rows < 8 ? 8 : rows);
+    if (rc) return rc;
+    const int e = (int)(p->ring_next++ % kRing);
+    if (p->ring_ev[e].recorded) HIPCHK(hipEventSynchronize(p->ring_ev[e].ev));
+    const size_t stride = (size_t)p->ring_rows * p->T;
+    const size_t n = (size_t)rows * p->T;
+    uint64_t *h = p->h_ptr + e * stride;
+    for (size_t i = 0; i < n; ++i) h[i] = (uint64_t)(uintptr_t)ptrs[i];
+    HIPCHK(hipMemcpyAsync(p->d_ptr + e * stride, h, n * sizeof(uint64_t), hipMemcpyHostToDevice, s));
+    *dev_tab = p->d_ptr + e * stride;
+    *entry = e;
+    return REFT_OK;
+}
+
+static int check_plan(const reft_plan *p, const char *who)
+{
+    if (!p) return fail(REFT_EINVAL, "%s: null plan", who);
+    if (p->host_only)
+        return fail(REFT_EINVAL, "%s: the plan was created host-only (no device tables)", who);
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev != p->device)
+        return fail(REFT_EINVAL, "%s: plan belongs to GPU %d but GPU %d is current", who,
+                    p->device, dev);
+    return REFT_OK;
+}
+
+static int check_span_ptrs(const reft_plan *p, const void *const *ptrs, uint32_t rows,
+                           const char *who)
+{
+    if (!ptrs) return fail(REFT_EINVAL, "%s: null pointer array", who);
+    for (uint32_t r = 0; r < rows; ++r)
+        for (uint64_t t = 0; t < p->T; ++t)
+            if (!ptrs[r * p->T + t] && p->off[t + 1] != p->off[t])
+                return fail(REFT_EINVAL, "%s: span %llu of shard %u is null but has %llu bytes",
+                            who, (unsigned long long)t, r,
+                            (unsigned long long)(p->off[t + 1] - p->off[t]));
+    return REFT_OK;
+}
+
+extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
+                                const uint64_t *bucket_nbytes, uint64_t NB,
+                                uint64_t uniform_bucket, reft_plan **out)
+{
+    if (!out) return fail(REFT_EINVAL, "reft_plan_create: null out");
+    *out = nullptr;
+    if (!span_nbytes || T == 0) return fail(REFT_EINVAL, "reft_plan_create: no spans");
+    if (T >= 0xffffffffull) return fail(REFT_EINVAL, "reft_plan_create: too many spans");
+
+    reft_plan *p = new (std::nothrow) reft_plan;
+    if (!p) return fail(REFT_EINVAL, "reft_plan_create: out of host memory");
+    struct Guard {
+        reft_plan *p;
+        ~Guard() { if (p) reft_plan_destroy(p); }
+    } guard{p};
+
+    p->T = T;
+    p->off.resize(T + 1);
+    p->off[0] = 0;
+    for (uint64_t t = 0; t < T; ++t)
+        if (__builtin_add_overflow(p->off[t], span_nbytes[t], &p->off[t + 1]))
+            return fail(REFT_ESIZE, "reft_plan_create: stream length overflows 64 bits");
+    p->L = p->off[T];
+
+    // buckets
+    p->bstart.push_back(0);
+    if (uniform_bucket) {
+        for (uint64_t b = 0; b < p->L; b += uniform_bucket)
+            p->bstart.push_back(b + uniform_bucket < p->L ? b + uniform_bucket : p->L);
+    } else if (!bucket_nbytes && NB == 0) {
+        if (p->L) p->bstart.push_back(p->L);              // no bucketing asked: one bucket
+    } else {
+        if (NB && !bucket_nbytes) return fail(REFT_EINVAL, "reft_plan_create: null bucket list");
+        uint64_t acc = 0;
+        for (uint64_t b = 0; b < NB; ++b) {
+            if (bucket_nbytes[b] == 0)
+                return fail(REFT_EINVAL, "reft_plan_create: bucket %llu has zero length",
+                            (unsigned long long)b);
+            if (__builtin_add_overflow(acc, bucket_nbytes[b], &acc) || acc > p->L)
+                return fail(REFT_ESIZE, "reft_plan_create: buckets exceed the stream length");
+            p->bstart.push_back(acc);
+        }
+        if (acc != p->L)
+            return fail(REFT_ESIZE, "reft_plan_create: buckets cover %llu of %llu stream bytes",
+                        (unsigned long long)acc, (unsigned long long)p->L);
+    }
+    p->NB = p->bstart.size() - 1;
+    for (uint64_t b = 0; b < p->NB; ++b)
+        if (p->bstart[b + 1] - p->bstart[b] > p->max_bucket)
+            p->max_bucket = p->bstart[b + 1] - p->bstart[b];
+
+    // tile table: first span that owns a byte of tile t (zero-length spans never qualify)
+    p->tile_shift = (uint32_t)g_tile_shift.load();
+    const uint64_t tile = 1ull << p->tile_shift;
+    p->ntiles = (p->L + tile - 1) >> p->tile_shift;
+    std::vector<uint32_t> &first = p->first;
+    first.assign(p->ntiles ? p->ntiles : 1, 0);
+    {
+        uint64_t i = 0;
+        for (uint64_t t = 0; t < p->ntiles; ++t) {
+            const uint64_t o = t << p->tile_shift;
+            while (p->off[i + 1] <= o) ++i;      // o < L = off[T] keeps i < T
+            first[t] = (uint32_t)i;
+        }
+    }
+
+    if (g_host_only.load()) {
+        p->host_only = true;
+        guard.p = nullptr;
+        *out = p;
+        return REFT_OK;
+    }
+    HIPCHK(hipGetDevice(&p->device));
+    hipDeviceProp_t prop;
+    HIPCHK(hipGetDeviceProperties(&prop, p->device));
+    p->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    HIPCHK(hipMalloc((void **)&p->d_off, (T + 1) * sizeof(uint64_t)));
+    HIPCHK(hipMalloc((void **)&p->d_first, first.size() * sizeof(uint32_t)));
+    HIPCHK(hipMemcpy(p->d_off, p->off.data(), (T + 1) * sizeof(uint64_t), hipMemcpyHostToDevice));
+    HIPCHK(hipMemcpy(p->d_first, first.data(), first.size() * sizeof(uint32_t),
+                     hipMemcpyHostToDevice));
+    int rc;
+    for (int i = 0; i < kRing; ++i)
+        if ((rc = make_event(p->ring_ev[i]))) return rc;
+    for (int i = 0; i < kMaxSlots; ++i) {
+        if ((rc = make_event(p->pack_filled[i])) || (rc = make_event(p->pack_free[i])) ||
+            (rc = make_event(p->rest_filled[i])) || (rc = make_event(p->rest_free[i])))
+            return rc;
+    }
+    if ((rc = make_event(p->pack_done)) || (rc = make_event(p->rest_done))) return rc;
+    if ((rc = ensure_ring(p, 8))) return rc;
+
+    guard.p = nullptr;
+    *out = p;
+    return REFT_OK;
+}
+
+extern "C" void reft_plan_destroy(reft_plan *p)
+{
+    if (!p) return;
+    // let everything that still reads the plan's tables finish
+    auto drain = [](Event &e) {
+        if (e.ev) {
+            if (e.recorded) (void)hipEventSynchronize(e.ev);
+            (void)hipEventDestroy(e.ev);
+            e.ev = nullptr;
+        }
+    };
+    for (int i = 0; i < kRing; ++i) drain(p->ring_ev[i]);
+    for (int i = 0; i < kMaxSlots; ++i) {
+        drain(p->pack_filled[i]);
+        drain(p->pack_free[i]);
+        drain(p->rest_filled[i]);
+        drain(p->rest_free[i]);
+    }
+    drain(p->pack_done);
+    drain(p->rest_done);
+    free_ring(p);
+    if (p->d_off) (void)hipFree(p->d_off);
+    if (p->d_first) (void)hipFree(p->d_first);
+    delete p;
+}
+
+extern "C" uint64_t reft_plan_stream_bytes(const reft_plan *p) { return p ? p->L : 0; }
+extern "C" uint64_t reft_plan_num_spans(const reft_plan *p) { return p ? p->T : 0; }
+extern "C" uint64_t reft_plan_num_buckets(const reft_plan *p) { return p ? p->NB : 0; }
+extern "C" uint64_t reft_plan_max_bucket_bytes(const reft_plan *p) { return p ? p->max_bucket : 0; }
+
+static uint64_t slot_stride(const reft_plan *p)
+{
+    // room for the bucket plus the sub-256-byte phase that keeps slot addresses congruent to
+    // stream offsets (so 16-byte-aligned spans stay aligned in the slot)
+    return (p->max_bucket + 256 + 255) & ~255ull;
+}
+
+extern "C" uint64_t reft_plan_staging_slot_bytes(const reft_plan *p)
+{
+    return p ? slot_stride(p) : 0;
+}
+
+extern "C" int reft_plan_bucket_range(const reft_plan *p, uint64_t b, uint64_t *begin,
+                                      uint64_t *end)
+{
+    if (!p || !begin || !end) return fail(REFT_EINVAL, "reft_plan_bucket_range: null argument");
+    if (b >= p->NB) return fail(REFT_EINVAL, "reft_plan_bucket_range: bucket %llu of %llu",
+                                (unsigned long long)b, (unsigned long long)p->NB);
+    *begin = p->bstart[b];
+    *end = p->bstart[b + 1];
+    return REFT_OK;
+}
+
+extern "C" int reft_plan_tile_info(const reft_plan *p, uint64_t *tile_bytes, uint64_t *ntiles)
+{
+    if (!p || !tile_bytes || !ntiles) return fail(REFT_EINVAL, "reft_plan_tile_info: null argument");
+    *tile_bytes = 1ull << p->tile_shift;
+    *ntiles = p->ntiles;
+    return REFT_OK;
+}
+
+extern "C" int reft_plan_tile_first_span(const reft_plan *p, uint64_t t, uint64_t *span)
+{
+    if (!p || !span) return fail(REFT_EINVAL, "reft_plan_tile_first_span: null argument");
+    if (t >= p->ntiles) return fail(REFT_EINVAL, "reft_plan_tile_first_span: tile out of range");
+    *span = p->first[t];
+    return REFT_OK;
+}
+
+extern "C" int reft_plan_span_offset(const reft_plan *p, uint64_t t, uint64_t *offset)
+{
+    if (!p || !offset) return fail(REFT_EINVAL, "reft_plan_span_offset: null argument");
+    if (t > p->T) return fail(REFT_EINVAL, "reft_plan_span_offset: span out of range");
+    *offset = p->off[t];
+    return REFT_OK;
+}
+
+extern "C" int reft_plan_split(const reft_plan *p, double t_bubble, double t_ss, uint64_t *cut)
+{
+    if (!p || !cut) return fail(REFT_EINVAL, "reft_plan_split: null argument");
+    if (!(t_ss > 0.0) || !(t_bubble >= 0.0))
+        return fail(REFT_EINVAL, "reft_plan_split: need t_ss > 0 and t_bubble >= 0");
+    const long double x = (long double)p->L * ((long double)t_bubble / (long double)t_ss);
+    *cut = x >= (long double)p->L ? p->L : (uint64_t)x;   // floor, clamped to L
+    return REFT_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// S1 + S2 + S3: snapshot
+// ------------------------------------------------------------------------------------------------
+static int staging_slots(const reft_plan *p, const void *staging, uint64_t staging_bytes,
+                         const char *who, int *nslots)
+{
+    if (p->NB == 0) {
+        *nslots = 1;
+        return REFT_OK;
+    }
+    if (!staging) return fail(REFT_EINVAL, "%s: null staging buffer", who);
+    if ((uintptr_t)staging & 255)
+        return fail(REFT_EINVAL, "%s: staging buffer must be 256-byte aligned", who);
+    const uint64_t n = staging_bytes / slot_stride(p);
+    if (n < 1)
+        return fail(REFT_ESIZE, "%s: staging has %llu bytes, one slot needs %llu", who,
+                    (unsigned long long)staging_bytes, (unsigned long long)slot_stride(p));
+    *nslots = n > (uint64_t)kMaxSlots ? kMaxSlots : (int)n;
+    return REFT_OK;
+}
+
+extern "C" int reft_snapshot_pack(reft_plan *p, const void *const *span_ptrs, void *staging,
+                                  uint64_t staging_bytes, void *host_dst, uint64_t host_cap,
+                                  reft_stream pack_stream, reft_stream copy_stream)
+{
+    int rc = check_plan(p, "reft_snapshot_pack");
+    if (rc) return rc;
+    if ((rc = check_span_ptrs(p, span_ptrs, 1, "reft_snapshot_pack"))) return rc;
+    if (host_cap < p->L)
+        return fail(REFT_ESIZE, "reft_snapshot_pack: host buffer holds %llu bytes, stream has %llu",
+                    (unsigned long long)host_cap, (unsigned long long)p->L);
+    if (p->L && !host_dst) return fail(REFT_EINVAL, "reft_snapshot_pack: null host buffer");
+    int nslots = 1;
+    if ((rc = staging_slots(p, staging, staging_bytes, "reft_snapshot_pack", &nslots))) return rc;
+    hipStream_t ps = (hipStream_t)pack_stream, cs = (hipStream_t)copy_stream;
+
+    const uint64_t *tab = nullptr;
+    int entry = 0;
+    if ((rc = upload_ptrs(p, span_ptrs, 1, ps, &tab, &entry))) return rc;
+    const LaunchCfg cfg = launch_cfg(p);
+    const PlanTables pt = p->tables();
+    const uint64_t stride = slot_stride(p);
+    for (uint64_t b = 0; b < p->NB; ++b) {
+        const int slot = (int)(b % (uint64_t)nslots);
+        const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
+        const uint64_t slot_addr = (uint64_t)(uintptr_t)staging + (uint64_t)slot * stride + (lo & 255);
+        // the slot's previous occupant must have left for the host
+        if ((rc = wait_on(ps, p->pack_free[slot]))) return rc;
+        HIPCHK(launch_gather(pt, tab, 1, false, slot_addr - lo, lo, hi, cfg, ps));
+        if ((rc = record(p->pack_filled[slot], ps))) return rc;
+        if ((rc = wait_on(cs, p->pack_filled[slot]))) return rc;
+        HIPCHK(hipMemcpyAsync((uint8_t *)host_dst + lo, (const void *)(uintptr_t)slot_addr, hi - lo,
+                              hipMemcpyDeviceToHost, cs));
+        if ((rc = record(p->pack_free[slot], cs))) return rc;
+    }
+    if ((rc = record(p->ring_ev[entry], ps))) return rc;
+    // completion: all buckets have landed once copy_stream reaches this point
+    if ((rc = wait_on(cs, p->ring_ev[entry]))) return rc;
+    return record(p->pack_done, cs);
+}
+
+extern "C" int reft_snapshot_wait(reft_plan *p)
+{
+    int rc = check_plan(p, "reft_snapshot_wait");
+    if (rc) return rc;
+    if (p->pack_done.recorded) HIPCHK(hipEventSynchronize(p->pack_done.ev));
+    return REFT_OK;
+}
+
+extern "C" int reft_snapshot_query(reft_plan *p)
+{
+    int rc = check_plan(p, "reft_snapshot_query");
+    if (rc) return rc;
+    if (!p->pack_done.recorded) return 1;
+    hipError_t e = hipEventQuery(p->pack_done.ev);
+    if (e == hipSuccess) return 1;
+    if (e == hipErrorNotReady) return 0;
+    return fail(REFT_EHIP, "hipEventQuery failed: %s", hipGetErrorString(e));
+}
+
+// ------------------------------------------------------------------------------------------------
+// S1 / S7 between device buffers
+// ------------------------------------------------------------------------------------------------
+extern "C" int reft_pack_device(reft_plan *p, const void *const *span_ptrs, void *dst_dev,
+                                uint64_t dst_cap, reft_stream stream)
+{
+    int rc = check_plan(p, "reft_pack_device");
+    if (rc) return rc;
+    if ((rc = check_span_ptrs(p, span_ptrs, 1, "reft_pack_device"))) return rc;
+    if (dst_cap < p->L) return fail(REFT_ESIZE, "reft_pack_device: destination too small");
+    if (p->L == 0) return REFT_OK;
+    if (!dst_dev) return fail(REFT_EINVAL, "reft_pack_device: null destination");
+    hipStream_t s = (hipStream_t)stream;
+    const uint64_t *tab = nullptr;
+    int entry = 0;
+    if ((rc = upload_ptrs(p, span_ptrs, 1, s, &tab, &entry))) return rc;
+    HIPCHK(launch_gather(p->tables(), tab, 1, false, (uint64_t)(uintptr_t)dst_dev, 0, p->L,
+                         launch_cfg(p), s));
+    return record(p->ring_ev[entry], s);
+}
+
+extern "C" int reft_unpack_device(reft_plan *p, const void *src_dev, uint64_t src_bytes,
+                                  void *const *span_ptrs, reft_stream stream)
+{
+    int rc = check_plan(p, "reft_unpack_device");
+    if (rc) return rc;
+    if ((rc = check_span_ptrs(p, span_ptrs, 1, "reft_unpack_device"))) return rc;
+    if (src_bytes != p->L)
+        return fail(REFT_ESIZE, "reft_unpack_device: source has %llu bytes, stream has %llu",
+                    (unsigned long long)src_bytes, (unsigned long long)p->L);
+    if (p->L == 0) return REFT_OK;
+    if (!src_dev) return fail(REFT_EINVAL, "reft_unpack_device: null source");
+    hipStream_t s = (hipStream_t)stream;
+    const uint64_t *tab = nullptr;
+    int entry = 0;
+    if ((rc = upload_ptrs(p, span_ptrs, 1, s, &tab, &entry))) return rc;
+    HIPCHK(launch_scatter(p->tables(), tab, (uint64_t)(uintptr_t)src_dev, 0, p->L, launch_cfg(p),
+                          s));
+    return record(p->ring_ev[entry], s);
+}
+
+// ------------------------------------------------------------------------------------------------
+// S4: parity over span tables
+// ------------------------------------------------------------------------------------------------
+extern "C" int reft_parity_encode(reft_plan *p, const void *const *shard_span_ptrs, uint32_t k,
+                                  void *parity_dev, reft_stream stream)
+{
+    int rc = check_plan(p, "reft_parity_encode");
+    if (rc) return rc;
+    if (k < 1 || k > REFT_MAX_K)
+        return fail(REFT_EINVAL, "reft_parity_encode: k = %u outside [1, %d]", k, REFT_MAX_K);
+    if ((rc = check_span_ptrs(p, shard_span_ptrs, k, "reft_parity_encode"))) return rc;
+    if (p->L == 0) return REFT_OK;
+    if (!parity_dev) return fail(REFT_EINVAL, "reft_parity_encode: null parity buffer");
+    hipStream_t s = (hipStream_t)stream;
+    const uint64_t *tab = nullptr;
+    int entry = 0;
+    if ((rc = upload_ptrs(p, shard_span_ptrs, k, s, &tab, &entry))) return rc;
+    const LaunchCfg cfg = launch_cfg(p);
+    const PlanTables pt = p->tables();
+    // up to kMaxSrc shards per pass; later passes fold further shards into the parity
+    uint32_t done = 0;
+    while (done < k) {
+        const bool acc = done > 0;
+        uint32_t rows = k - done;
+        const uint32_t cap = (uint32_t)kMaxSrc - (acc ? 1u : 0u);
+        if (rows > cap) rows = cap;
+        HIPCHK(launch_gather(pt, tab + (uint64_t)done * p->T, (int)rows, acc,
+                             (uint64_t)(uintptr_t)parity_dev, 0, p->L, cfg, s));
+        done += rows;
+    }
+    return record(p->ring_ev[entry], s);
+}
+
+// ------------------------------------------------------------------------------------------------
+// S6: single-loss decode
+// ------------------------------------------------------------------------------------------------
+extern "C" int reft_reconstruct(const void *const *shards, uint32_t k, const void *parity,
+                                uint64_t L, void *out_dev, uint32_t *lost_index,
+                                reft_stream stream)
+{
+    if (!shards) return fail(REFT_EINVAL, "reft_reconstruct: null shard array");
+    if (k < 1 || k > REFT_MAX_K - 1)
+        return fail(REFT_EINVAL, "reft_reconstruct: k = %u outside [1, %d]", k, REFT_MAX_K - 1);
+    uint32_t nlost = 0, lost = 0;
+    for (uint32_t s = 0; s < k; ++s)
+        if (!shards[s]) {
+            if (nlost == 0) lost = s;
+            ++nlost;
+        }
+    if (nlost >= 2)
+        return fail(REFT_EUNRECOVERABLE,
+                    "reft_reconstruct: %u of %u shards are lost; one parity decodes one loss",
+                    nlost, k);
+    if (nlost == 0) return fail(REFT_EINVAL, "reft_reconstruct: no shard is marked lost (NULL)");
+    if (lost_index) *lost_index = lost;
+    if (L == 0) return REFT_OK;
+    if (!parity || !out_dev) return fail(REFT_EINVAL, "reft_reconstruct: null parity or output");
+
+    uint64_t src[REFT_MAX_K];
+    uint32_t n = 0;
+    src[n++] = (uint64_t)(uintptr_t)parity;
+    for (uint32_t s = 0; s < k; ++s)
+        if (shards[s]) src[n++] = (uint64_t)(uintptr_t)shards[s];
+
+    const LaunchCfg cfg = launch_cfg(nullptr);
+    const uint32_t tile_shift = (uint32_t)g_tile_shift.load();
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t done = 0;
+    while (done < n) {
+        SrcBases b{};
+        int m = 0;
+        if (done > 0) b.p[m++] = (uint64_t)(uintptr_t)out_dev;     // fold into the partial result
+        while (m < kMaxSrc && done < n) b.p[m++] = src[done++];
+        HIPCHK(launch_xor_contig(b, m, (uint64_t)(uintptr_t)out_dev, L, tile_shift, cfg, st));
+    }
+    return REFT_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// S5 + S7: restore
+// ------------------------------------------------------------------------------------------------
+extern "C" int reft_restore(reft_plan *p, const void *host_src, uint64_t host_bytes, void *staging,
+                            uint64_t staging_bytes, void *const *span_ptrs,
+                            reft_stream copy_stream, reft_stream unpack_stream)
+{
+    int rc = check_plan(p, "reft_restore");
+    if (rc) return rc;
+    if ((rc = check_span_ptrs(p, span_ptrs, 1, "reft_restore"))) return rc;
+    if (host_bytes != p->L)
+        return fail(REFT_ESIZE, "reft_restore: host snapshot has %llu bytes, stream has %llu",
+                    (unsigned long long)host_bytes, (unsigned long long)p->L);
+    if (p->L && !host_src) return fail(REFT_EINVAL, "reft_restore: null host buffer");
+    int nslots = 1;
+    if ((rc = staging_slots(p, staging, staging_bytes, "reft_restore", &nslots))) return rc;
+    hipStream_t cs = (hipStream_t)copy_stream, us = (hipStream_t)unpack_stream;
+
+    const uint64_t *tab = nullptr;
+    int entry = 0;
+    if ((rc = upload_ptrs(p, span_ptrs, 1, us, &tab, &entry))) return rc;
+    const LaunchCfg cfg = launch_cfg(p);
+    const PlanTables pt = p->tables();
+    const uint64_t stride = slot_stride(p);
+    for (uint64_t b = 0; b < p->NB; ++b) {
+        const int slot = (int)(b % (uint64_t)nslots);
+        const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
+        const uint64_t slot_addr = (uint64_t)(uintptr_t)staging + (uint64_t)slot * stride + (lo & 255);
+        // the slot's previous occupant must have been scattered
+        if ((rc = wait_on(cs, p->rest_free[slot]))) return rc;
+        HIPCHK(hipMemcpyAsync((void *)(uintptr_t)slot_addr, (const uint8_t *)host_src + lo, hi - lo,
+                              hipMemcpyHostToDevice, cs));
+        if ((rc = record(p->rest_filled[slot], cs))) return rc;
+        if ((rc = wait_on(us, p->rest_filled[slot]))) return rc;
+        HIPCHK(launch_scatter(pt, tab, slot_addr - lo, lo, hi, cfg, us));
+        if ((rc = record(p->rest_free[slot], us))) return rc;
+    }
+    if ((rc = record(p->ring_ev[entry], us))) return rc;
+    return record(p->rest_done, us);
+}
+
+extern "C" int reft_restore_wait(reft_plan *p)
+{
+    int rc = check_plan(p, "reft_restore_wait");
+    if (rc) return rc;
+    if (p->rest_done.recorded) HIPCHK(hipEventSynchronize(p->rest_done.ev));
+    return REFT_OK;
+}

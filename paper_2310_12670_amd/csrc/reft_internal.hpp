@@ -1,0 +1,47 @@
+// Internal interface between the C-ABI host logic (reft_api.hip) and the kernels
+// (reft_kernels.hip).  Not installed; the public boundary is include/reft.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace reft {
+
+constexpr int kThreads = 256;      // 4 wavefronts of 64 lanes per workgroup
+constexpr int kMaxSrc = 8;         // sources XORed by one launch; more are chained
+
+struct LaunchCfg {
+    uint32_t max_wgs;              // cap on the grid size (>= 1)
+    uint32_t unroll;               // 1, 2 or 4 chunks of 16 B in flight per thread and source
+    bool nontemporal;
+};
+
+// Device-side tables of a plan.
+struct PlanTables {
+    const uint64_t *off;           // [T+1] prefix sums of the span sizes (stream offsets)
+    const uint32_t *first_span;    // [ntiles] first span that owns a byte of tile t
+    uint64_t T;
+    uint64_t L;
+    uint32_t tile_shift;           // tile = 1 << tile_shift stream bytes
+};
+
+// Sources passed by value for the contiguous XOR kernel.
+struct SrcBases {
+    uint64_t p[kMaxSrc];
+};
+
+// dst_vbase + o is the destination address of stream byte o, for o in [lo, hi).
+// tab holds nrows rows of T span pointers (row stride T); the kernel XORs the rows' streams and,
+// if acc, the destination's current contents.  nrows + acc <= kMaxSrc.
+hipError_t launch_gather(const PlanTables &pt, const uint64_t *tab, int nrows, bool acc,
+                         uint64_t dst_vbase, uint64_t lo, uint64_t hi, const LaunchCfg &cfg,
+                         hipStream_t stream);
+
+// src_vbase + o is the source address of stream byte o; tab is one row of T span pointers.
+hipError_t launch_scatter(const PlanTables &pt, const uint64_t *tab, uint64_t src_vbase,
+                          uint64_t lo, uint64_t hi, const LaunchCfg &cfg, hipStream_t stream);
+
+// dst[i] = XOR over s < nsrc of src.p[s][i], i in [0, L); any alignment.
+hipError_t launch_xor_contig(const SrcBases &src, int nsrc, uint64_t dst, uint64_t L,
+                             uint32_t tile_shift, const LaunchCfg &cfg, hipStream_t stream);
+
+}  // namespace reft

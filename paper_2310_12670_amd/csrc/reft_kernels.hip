@@ -1,0 +1,300 @@
+// HIP kernels of libreft for gfx950 (CDNA4): ragged gather (snapshot pack and in-place XOR parity
+// over span tables), ragged scatter (restore) and contiguous k-way XOR (single-loss decode).
+//
+// All three are HBM-streaming kernels: no arithmetic beyond a 128-bit XOR per 16 bytes and
+// source, so the design goal is full-width, coalesced 16-byte accesses with enough of them in
+// flight per compute unit.  A workgroup is 256 threads (4 wavefronts of 64).  Work is cut into
+// tiles of 2^tile_shift consecutive stream bytes; a launch walks its tiles with a grid-stride loop
+// so the grid size (and with it the number of compute units a snapshot occupies next to training
+// kernels) is a free parameter.  Consecutive workgroups take consecutive tiles, so the eight XCDs
+// (workgroups are dealt to them round-robin) stream through neighbouring addresses together.
+//
+// Operations (bytes only; see include/reft.h for the paper passages):
+//   gather  dst[o] = XOR_s span_s(o)          stream offset o in [lo, hi), spans via pointer tables
+//   scatter span(o) = src[o]
+//   contig  dst[i] = XOR_s src_s[i]
+#include "reft_internal.hpp"
+
+namespace reft {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// Addresses travel through the kernels as integers (a destination may be a "virtual base" that
+// only becomes a valid address once a stream offset is added).  They are turned into pointers in
+// the global address space here, so that the accesses compile to global_load / global_store.
+#define REFT_GLOBAL __attribute__((address_space(1)))
+typedef const REFT_GLOBAL u32x4 *gcptr16;
+typedef REFT_GLOBAL u32x4 *gptr16;
+
+__device__ __forceinline__ gcptr16 as_gc16(uint64_t a) { return (gcptr16)a; }
+__device__ __forceinline__ gptr16 as_g16(uint64_t a) { return (gptr16)a; }
+__device__ __forceinline__ uint8_t ld8(uint64_t a) { return *(const REFT_GLOBAL uint8_t *)a; }
+__device__ __forceinline__ void st8(uint64_t a, uint8_t v) { *(REFT_GLOBAL uint8_t *)a = v; }
+
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16(gcptr16 p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <bool NT>
+__device__ __forceinline__ void st16(gptr16 p, u32x4 v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// The 16 bytes that start r bytes (0 < r < 16) into the 32 bytes lo || hi (little endian).
+__device__ __forceinline__ u32x4 shift_bytes(u32x4 lo, u32x4 hi, uint32_t r)
+{
+    const uint32_t q = r >> 2, b = (r & 3u) * 8u;
+    uint32_t x0, x1, x2, x3, x4;
+    switch (q) {
+    case 0:  x0 = lo.x; x1 = lo.y; x2 = lo.z; x3 = lo.w; x4 = hi.x; break;
+    case 1:  x0 = lo.y; x1 = lo.z; x2 = lo.w; x3 = hi.x; x4 = hi.y; break;
+    case 2:  x0 = lo.z; x1 = lo.w; x2 = hi.x; x3 = hi.y; x4 = hi.z; break;
+    default: x0 = lo.w; x1 = hi.x; x2 = hi.y; x3 = hi.z; x4 = hi.w; break;
+    }
+    if (b) {
+        x0 = (x0 >> b) | (x1 << (32u - b));
+        x1 = (x1 >> b) | (x2 << (32u - b));
+        x2 = (x2 >> b) | (x3 << (32u - b));
+        x3 = (x3 >> b) | (x4 << (32u - b));
+    }
+    u32x4 v = {x0, x1, x2, x3};
+    return v;
+}
+
+// 16 source bytes at byte address addr + 16*c for any alignment of addr, using only aligned
+// 16-byte loads.  Both aligned blocks that are read contain at least one of the wanted bytes, so
+// no load reaches outside the 16-byte-aligned hull of the source range.
+template <bool NT>
+__device__ __forceinline__ u32x4 load_any(uint64_t addr, uint32_t c)
+{
+    const uint32_t r = (uint32_t)addr & 15u;
+    gcptr16 a = as_gc16(addr - r) + c;
+    const u32x4 lo = ld16<NT>(a);
+    if (r == 0) return lo;
+    const u32x4 hi = ld16<NT>(a + 1);
+    return shift_bytes(lo, hi, r);
+}
+
+// One piece: n bytes at destination address d = XOR of the n bytes at each source address s[j].
+// The whole workgroup cooperates.  Destination stores are 16-byte aligned: up to 15 head bytes
+// and 15 tail bytes are moved bytewise, the body as 16-byte chunks.  If every source is
+// co-aligned with the destination (the case for tensors whose sizes and addresses are multiples
+// of 16) the body is plain vector loads, U chunks in flight per thread and source; otherwise each
+// misaligned source is read as two aligned chunks and byte-shifted in registers.
+template <int K, int U, bool NT>
+__device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], uint32_t n)
+{
+    const uint32_t tid = threadIdx.x;
+    uint32_t head = (uint32_t)(0 - d) & 15u;
+    if (head > n) head = n;
+    const uint32_t body = n - head;
+    const uint32_t nb = body >> 4;
+    const uint32_t tail = body & 15u;
+
+    if (tid < 32) {
+        uint32_t i = 0xffffffffu;
+        if (tid < head) i = tid;
+        else if (tid >= 16 && tid - 16 < tail) i = head + (nb << 4) + (tid - 16);
+        if (i != 0xffffffffu) {
+            uint8_t v = ld8(s[0] + i);
+#pragma unroll
+            for (int j = 1; j < K; ++j) v ^= ld8(s[j] + i);
+            st8(d + i, v);
+        }
+    }
+    if (nb == 0) return;
+
+    gptr16 dp = as_g16(d + head);
+    uint32_t mis = 0;
+#pragma unroll
+    for (int j = 0; j < K; ++j) mis |= (uint32_t)(s[j] + head) & 15u;
+
+    if (mis == 0) {
+        gcptr16 sp[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) sp[j] = as_gc16(s[j] + head);
+        constexpr uint32_t step = kThreads * U;
+        const uint32_t full = nb / step * step;
+        for (uint32_t c = tid; c < full; c += step) {
+            u32x4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = ld16<NT>(sp[0] + c + u * kThreads);
+#pragma unroll
+            for (int j = 1; j < K; ++j) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[u] ^= ld16<NT>(sp[j] + c + u * kThreads);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) st16<NT>(dp + c + u * kThreads, v[u]);
+        }
+        for (uint32_t c = full + tid; c < nb; c += kThreads) {
+            u32x4 v = ld16<NT>(sp[0] + c);
+#pragma unroll
+            for (int j = 1; j < K; ++j) v ^= ld16<NT>(sp[j] + c);
+            st16<NT>(dp + c, v);
+        }
+    } else {
+        for (uint32_t c = tid; c < nb; c += kThreads) {
+            u32x4 v = load_any<NT>(s[0] + head, c);
+#pragma unroll
+            for (int j = 1; j < K; ++j) v ^= load_any<NT>(s[j] + head, c);
+            st16<NT>(dp + c, v);
+        }
+    }
+}
+
+// dst_vbase + o  <-  XOR over rows j < K of (tab[j*T + span(o)] + offset of o in its span);
+// with acc != 0 only K-1 rows are read and the destination itself is the K-th source.
+template <int K, int U, bool NT>
+__global__ void __launch_bounds__(kThreads)
+k_gather(PlanTables pt, const uint64_t *__restrict__ tab, uint64_t dst_vbase, uint64_t lo,
+         uint64_t hi, uint32_t acc)
+{
+    const uint32_t sh = pt.tile_shift;
+    const uint64_t t_last = (hi - 1) >> sh;
+    for (uint64_t t = (lo >> sh) + blockIdx.x; t <= t_last; t += gridDim.x) {
+        uint64_t o = t << sh;
+        uint64_t e = o + (1ull << sh);
+        if (o < lo) o = lo;
+        if (e > hi) e = hi;
+        uint32_t i = pt.first_span[t];
+        while (o < e) {
+            // o < e <= L = off[T], so a span with off[i+1] > o exists at or after i
+            while (pt.off[i + 1] <= o) ++i;
+            const uint64_t so = pt.off[i];
+            uint64_t pe = pt.off[i + 1];
+            if (pe > e) pe = e;
+            uint64_t s[K];
+#pragma unroll
+            for (int j = 0; j < K - 1; ++j) s[j] = tab[(uint64_t)j * pt.T + i] + (o - so);
+            // accumulate mode: the destination's current bytes are the last source (each byte
+            // is read and then written by the same thread, so in-place is safe)
+            s[K - 1] = acc ? dst_vbase + o : tab[(uint64_t)(K - 1) * pt.T + i] + (o - so);
+            xor_piece<K, U, NT>(dst_vbase + o, s, (uint32_t)(pe - o));
+            o = pe;
+        }
+    }
+}
+
+// tab[span(o)] + offset of o in its span  <-  src_vbase + o
+template <int U, bool NT>
+__global__ void __launch_bounds__(kThreads)
+k_scatter(PlanTables pt, const uint64_t *__restrict__ tab, uint64_t src_vbase, uint64_t lo,
+          uint64_t hi)
+{
+    const uint32_t sh = pt.tile_shift;
+    const uint64_t t_last = (hi - 1) >> sh;
+    for (uint64_t t = (lo >> sh) + blockIdx.x; t <= t_last; t += gridDim.x) {
+        uint64_t o = t << sh;
+        uint64_t e = o + (1ull << sh);
+        if (o < lo) o = lo;
+        if (e > hi) e = hi;
+        uint32_t i = pt.first_span[t];
+        while (o < e) {
+            while (pt.off[i + 1] <= o) ++i;
+            const uint64_t so = pt.off[i];
+            uint64_t pe = pt.off[i + 1];
+            if (pe > e) pe = e;
+            const uint64_t s[1] = {src_vbase + o};
+            xor_piece<1, U, NT>(tab[i] + (o - so), s, (uint32_t)(pe - o));
+            o = pe;
+        }
+    }
+}
+
+// dst[i] = XOR_j src.p[j][i], i in [0, L)
+template <int K, int U, bool NT>
+__global__ void __launch_bounds__(kThreads)
+k_xor_contig(SrcBases src, uint64_t dst, uint64_t L, uint32_t sh)
+{
+    const uint64_t ntiles = (L + (1ull << sh) - 1) >> sh;
+    for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const uint64_t o = t << sh;
+        uint64_t n = L - o;
+        if (n > (1ull << sh)) n = 1ull << sh;
+        uint64_t s[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) s[j] = src.p[j] + o;
+        xor_piece<K, U, NT>(dst + o, s, (uint32_t)n);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// launch wrappers: pick the instantiation for (number of sources, unroll, non-temporal)
+// ------------------------------------------------------------------------------------------------
+static uint32_t grid_for(uint64_t ntiles, const LaunchCfg &cfg)
+{
+    uint64_t g = ntiles < cfg.max_wgs ? ntiles : cfg.max_wgs;
+    return (uint32_t)(g < 1 ? 1 : g);
+}
+
+#define REFT_PICK_UNT(KERNEL, K)                                                                  \
+    (cfg.nontemporal                                                                              \
+         ? (cfg.unroll == 1 ? KERNEL<K, 1, true> : cfg.unroll == 2 ? KERNEL<K, 2, true>           \
+                                                                   : KERNEL<K, 4, true>)          \
+         : (cfg.unroll == 1 ? KERNEL<K, 1, false> : cfg.unroll == 2 ? KERNEL<K, 2, false>         \
+                                                                    : KERNEL<K, 4, false>))
+
+#define REFT_PICK_K(KERNEL, fn, nsrc)                                                             \
+    switch (nsrc) {                                                                               \
+    case 1: fn = REFT_PICK_UNT(KERNEL, 1); break;                                                 \
+    case 2: fn = REFT_PICK_UNT(KERNEL, 2); break;                                                 \
+    case 3: fn = REFT_PICK_UNT(KERNEL, 3); break;                                                 \
+    case 4: fn = REFT_PICK_UNT(KERNEL, 4); break;                                                 \
+    case 5: fn = REFT_PICK_UNT(KERNEL, 5); break;                                                 \
+    case 6: fn = REFT_PICK_UNT(KERNEL, 6); break;                                                 \
+    case 7: fn = REFT_PICK_UNT(KERNEL, 7); break;                                                 \
+    case 8: fn = REFT_PICK_UNT(KERNEL, 8); break;                                                 \
+    default: return hipErrorInvalidValue;                                                         \
+    }
+
+hipError_t launch_gather(const PlanTables &pt, const uint64_t *tab, int nrows, bool acc,
+                         uint64_t dst_vbase, uint64_t lo, uint64_t hi, const LaunchCfg &cfg,
+                         hipStream_t stream)
+{
+    if (lo >= hi) return hipSuccess;
+    if (hi > pt.L) return hipErrorInvalidValue;
+    void (*fn)(PlanTables, const uint64_t *, uint64_t, uint64_t, uint64_t, uint32_t) = nullptr;
+    const int nsrc = nrows + (acc ? 1 : 0);
+    REFT_PICK_K(k_gather, fn, nsrc)
+    const uint64_t ntiles = ((hi - 1) >> pt.tile_shift) - (lo >> pt.tile_shift) + 1;
+    hipLaunchKernelGGL(fn, dim3(grid_for(ntiles, cfg)), dim3(kThreads), 0, stream, pt, tab,
+                       dst_vbase, lo, hi, acc ? 1u : 0u);
+    return hipGetLastError();
+}
+
+hipError_t launch_scatter(const PlanTables &pt, const uint64_t *tab, uint64_t src_vbase,
+                          uint64_t lo, uint64_t hi, const LaunchCfg &cfg, hipStream_t stream)
+{
+    if (lo >= hi) return hipSuccess;
+    if (hi > pt.L) return hipErrorInvalidValue;
+    void (*fn)(PlanTables, const uint64_t *, uint64_t, uint64_t, uint64_t) =
+        cfg.nontemporal
+            ? (cfg.unroll == 1 ? k_scatter<1, true> : cfg.unroll == 2 ? k_scatter<2, true>
+                                                                      : k_scatter<4, true>)
+            : (cfg.unroll == 1 ? k_scatter<1, false> : cfg.unroll == 2 ? k_scatter<2, false>
+                                                                       : k_scatter<4, false>);
+    const uint64_t ntiles = ((hi - 1) >> pt.tile_shift) - (lo >> pt.tile_shift) + 1;
+    hipLaunchKernelGGL(fn, dim3(grid_for(ntiles, cfg)), dim3(kThreads), 0, stream, pt, tab,
+                       src_vbase, lo, hi);
+    return hipGetLastError();
+}
+
+hipError_t launch_xor_contig(const SrcBases &src, int nsrc, uint64_t dst, uint64_t L,
+                             uint32_t tile_shift, const LaunchCfg &cfg, hipStream_t stream)
+{
+    if (L == 0) return hipSuccess;
+    void (*fn)(SrcBases, uint64_t, uint64_t, uint32_t) = nullptr;
+    REFT_PICK_K(k_xor_contig, fn, nsrc)
+    const uint64_t ntiles = (L + (1ull << tile_shift) - 1) >> tile_shift;
+    hipLaunchKernelGGL(fn, dim3(grid_for(ntiles, cfg)), dim3(kThreads), 0, stream, src, dst, L,
+                       tile_shift);
+    return hipGetLastError();
+}
+
+}  // namespace reft
