@@ -1,0 +1,384 @@
+#!/usr/bin/env python3
+"""Benchmark of the in-memory checkpointing hot path on one MI355X.
+
+One *step* is one pass of the whole path over one rank-shaped synthetic state, inputs resident in
+HBM before the clock starts:
+
+  save   reft_snapshot_pack   own shard   -> staging ring -> pinned host      (gather + D2H)
+         reft_parity_encode   k shards    -> parity (device)                  (k-way XOR, in place)
+         reft_snapshot_pack   parity      -> pinned host                      (gather + D2H)
+  load   reft_restore         host shard  -> staging ring -> fresh tensors    (H2D + scatter)
+         reft_restore         host parity -> device                           (H2D + scatter)
+         reft_reconstruct_spans  k-1 survivors + parity -> lost shard's tensors (k-way XOR)
+
+``value`` is the step's checkpoint traffic, 4*L bytes (shard + parity saved to host, shard + parity
+loaded back), divided by the step time: the path is bound by the host link, which is why the
+HBM-bound kernels are reported separately under ``stages`` and ``roofline``.
+
+The last line printed is the JSON record.  ``python bench.py --help`` lists the options.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E, published
+LINK_PEAK_GBPS = 63.0            # PCIe Gen5 x16, one direction: 32 GT/s * 16 * 128/130 / 8
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawTextHelpFormatter)
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=1, help="workload configuration 0..4 (default 1)")
+    ap.add_argument("--gemm-seconds", type=float, default=0.0,
+                    help="length of the bf16 GEMM proxy loop for the slowdown figure "
+                         "(0 = as long as one save phase; negative = skip)")
+    ap.add_argument("--snapshot-wgs", type=int, default=0,
+                    help="cap on workgroups of the snapshot kernels while the GEMM proxy runs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-mib", type=int, default=512,
+                    help="bytes per shard of the CPU-oracle sample, MiB")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU (the simulated node's k shards live in one "
+              "GPU's HBM); --gpus N with N > 1 is not supported.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2310_12670_amd as reft
+    from workload import fill_shard, make_workload, span_nbytes
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU path)"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = make_workload(args.config)
+    k, L, T = wl.k, wl.L, len(wl.spans)
+    sizes = span_nbytes(wl)
+    lost = wl.lost
+    own = (lost + 1) % k
+    log(f"[bench] config {wl.cfg}: {wl.description}; k={k} T={T} L={L} buckets={len(wl.bucket_nbytes)} "
+        f"lost={lost} own={own}")
+
+    t0 = time.time()
+    shards = [fill_shard(wl, s, dev) for s in range(k)]
+    torch.cuda.synchronize()
+    log(f"[bench] generated {k * L / 1e9:.1f} GB of state in {time.time() - t0:.1f} s")
+
+    plan = reft.reft_plan_create(sizes, wl.bucket_nbytes)
+    bucket = reft.reft_plan_max_bucket_bytes(plan)
+    pplan = reft.reft_plan_create([L], None, bucket)           # the parity as a 1-span shard
+    nslots = 4
+    def ring(p):
+        return torch.empty(nslots * reft.reft_plan_staging_slot_bytes(p), dtype=torch.uint8, device=dev)
+    stag_save, stag_psave, stag_load, stag_pload = ring(plan), ring(pplan), ring(plan), ring(pplan)
+    t0 = time.time()
+    host_snap = torch.empty(L, dtype=torch.uint8, pin_memory=True)
+    host_par = torch.empty(L, dtype=torch.uint8, pin_memory=True)
+    log(f"[bench] pinned {2 * L / 1e9:.1f} GB of host memory in {time.time() - t0:.1f} s")
+    parity = torch.empty(L, dtype=torch.uint8, device=dev)
+    parity2 = torch.empty(L, dtype=torch.uint8, device=dev)
+    fresh_own = [torch.empty_like(t) for t in shards[own]]
+    fresh_lost = [torch.empty_like(t) for t in shards[lost]]
+
+    p_own = reft.ptr_array(shards[own])
+    p_all = reft.ptr_array([t for sh in shards for t in sh])
+    p_surv = reft.ptr_array([None if s == lost else t for s, sh in enumerate(shards) for t in sh])
+    p_fresh_own = reft.ptr_array(fresh_own)
+    p_fresh_lost = reft.ptr_array(fresh_lost)
+    p_par = reft.ptr_array([parity])
+    p_par2 = reft.ptr_array([parity2])
+
+    s_pack, s_copy, s_xor, s_h2d, s_unpack = (torch.cuda.Stream() for _ in range(5))
+    enc_events, rec_events = [], []
+
+    def save_phase(timed):
+        reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_pack, s_copy)
+        if timed:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(s_xor)
+        reft.reft_parity_encode(plan, p_all, k, parity, s_xor)
+        if timed:
+            e1.record(s_xor)
+            enc_events.append((e0, e1))
+        s_pack.wait_stream(s_xor)
+        reft.reft_snapshot_pack(pplan, p_par, stag_psave, host_par, s_pack, s_copy)
+
+    def load_phase(timed):
+        s_h2d.wait_stream(s_copy)                  # the snapshot is complete on the host
+        reft.reft_restore(plan, host_snap, stag_load, p_fresh_own, s_h2d, s_unpack)
+        reft.reft_restore(pplan, host_par, stag_pload, p_par2, s_h2d, s_unpack)
+        s_xor.wait_stream(s_unpack)
+        if timed:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(s_xor)
+        reft.reft_reconstruct_spans(plan, p_surv, k, lost, parity2, p_fresh_lost, s_xor)
+        if timed:
+            e1.record(s_xor)
+            rec_events.append((e0, e1))
+        # the next step's save may not overwrite what this step's load still reads
+        s_pack.wait_stream(s_xor)
+        s_copy.wait_stream(s_h2d)
+
+    def step(timed=False):
+        save_phase(timed)
+        load_phase(timed)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(timed=True)
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t0
+    ms_per_step = t_total / args.steps * 1e3
+    value = 4 * L / (t_total / args.steps) / 1e9
+
+    # ---- results are what they should be (device-side comparison with the source tensors) ------
+    verified = all(torch.equal(a, b) for a, b in zip(fresh_own, shards[own])) and \
+        all(torch.equal(a, b) for a, b in zip(fresh_lost, shards[lost]))
+    if not verified:
+        log("[bench] ERROR: restored or reconstructed tensors differ from the originals")
+
+    enc_ms = sum(a.elapsed_time(b) for a, b in enc_events) / len(enc_events)
+    rec_ms = sum(a.elapsed_time(b) for a, b in rec_events) / len(rec_events)
+    enc_gbps = (k + 1) * L / (enc_ms * 1e-3) / 1e9
+    rec_gbps = (k + 1) * L / (rec_ms * 1e-3) / 1e9
+
+    # ---- each stage alone --------------------------------------------------------------------
+    def timed_alone(fn, stream, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e-3)
+        ts.sort()
+        return ts[len(ts) // 2]
+
+    packed = torch.empty(L, dtype=torch.uint8, device=dev)
+    t_pack = timed_alone(lambda: reft.reft_pack_device(plan, p_own, packed, s_xor), s_xor)
+    t_unpack = timed_alone(lambda: reft.reft_unpack_device(plan, packed, p_fresh_own, s_xor), s_xor)
+    t_enc = timed_alone(lambda: reft.reft_parity_encode(plan, p_all, k, parity, s_xor), s_xor)
+    t_rec = timed_alone(lambda: reft.reft_reconstruct_spans(plan, p_surv, k, lost, parity2,
+                                                            p_fresh_lost, s_xor), s_xor)
+    del packed
+
+    def snap():
+        reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_pack, s_copy)
+        s_xor.wait_stream(s_copy)
+    def rest():
+        s_h2d.wait_stream(s_xor)
+        reft.reft_restore(plan, host_snap, stag_load, p_fresh_own, s_h2d, s_unpack)
+        s_xor.wait_stream(s_unpack)
+    s_pack.wait_stream(s_xor)
+    t_snap = timed_alone(lambda: (s_pack.wait_stream(s_xor), snap()), s_xor, reps=3)
+    t_rest = timed_alone(rest, s_xor, reps=3)
+
+    def pct(x, peak):
+        return round(100.0 * x / peak, 1)
+    stages = {
+        "pack_kernel_GBps": round(2 * L / t_pack / 1e9, 1),
+        "unpack_kernel_GBps": round(2 * L / t_unpack / 1e9, 1),
+        "parity_encode_GBps": round((k + 1) * L / t_enc / 1e9, 1),
+        "reconstruct_GBps": round((k + 1) * L / t_rec / 1e9, 1),
+        "snapshot_d2h_GBps": round(L / t_snap / 1e9, 2),
+        "restore_h2d_GBps": round(L / t_rest / 1e9, 2),
+    }
+    stages["pct_hbm_peak"] = {n: pct(stages[n], HBM_PEAK_GBPS) for n in
+                              ("pack_kernel_GBps", "unpack_kernel_GBps", "parity_encode_GBps",
+                               "reconstruct_GBps")}
+    stages["pct_link_peak"] = {n: pct(stages[n], LINK_PEAK_GBPS) for n in
+                               ("snapshot_d2h_GBps", "restore_h2d_GBps")}
+
+    # ---- concurrent training proxy: bf16 8192^3 GEMMs beside the save phase -------------------
+    gemm = None
+    if args.gemm_seconds >= 0:
+        n = 8192
+        A = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
+        B = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
+        C = torch.empty(n, n, device=dev, dtype=torch.bfloat16)
+        cur = torch.cuda.current_stream()
+
+        def gemms(count):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(cur)
+            for _ in range(count):
+                torch.matmul(A, B, out=C)
+            e1.record(cur)
+            return e0, e1
+
+        e0, e1 = gemms(20)
+        torch.cuda.synchronize()
+        e0, e1 = gemms(50)
+        torch.cuda.synchronize()
+        t_one = e0.elapsed_time(e1) * 1e-3 / 50
+        # the save phase alone
+        torch.cuda.synchronize()
+        ts0 = time.perf_counter()
+        save_phase(False)
+        torch.cuda.synchronize()
+        t_save = time.perf_counter() - ts0
+        span = args.gemm_seconds if args.gemm_seconds > 0 else t_save
+        count = max(10, int(span / t_one))
+        e0, e1 = gemms(count)
+        torch.cuda.synchronize()
+        t_alone = e0.elapsed_time(e1) * 1e-3
+        if args.snapshot_wgs:
+            reft.reft_set_tunable("max_wgs", args.snapshot_wgs)
+        torch.cuda.synchronize()
+        ts0 = time.perf_counter()
+        save_phase(False)
+        e0, e1 = gemms(count)
+        e1.synchronize()
+        t_with = e0.elapsed_time(e1) * 1e-3
+        torch.cuda.synchronize()
+        t_save_with = time.perf_counter() - ts0
+        reft.reft_set_tunable("max_wgs", 0)
+        gemm = {
+            "gemm": "bf16 8192x8192x8192 (torch.matmul as the load)",
+            "gemms": count,
+            "tflops_alone": round(2 * n ** 3 * count / t_alone / 1e12, 1),
+            "t_alone_s": round(t_alone, 4),
+            "t_with_snapshot_s": round(t_with, 4),
+            "slowdown_pct": round(100.0 * (t_with - t_alone) / t_alone, 2),
+            "save_phase_alone_s": round(t_save, 4),
+            "save_phase_with_gemm_s": round(t_save_with, 4),
+            "snapshot_wgs": args.snapshot_wgs,
+        }
+        del A, B, C
+
+    # ---- the CPU oracle on a bounded sample of the same workload --------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(wl, shards, own, lost, args.cpu_sample_mib << 20)
+
+    record = {
+        "metric": "snapshot+parity GB/s (% HBM/host-link peak); concurrent step slowdown %",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 2),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {
+            "workload": f"config {wl.cfg}: {wl.description}",
+            "k": k, "spans": T, "stream_bytes": L, "buckets": len(wl.bucket_nbytes),
+            "step": "snapshot own shard + XOR parity + snapshot parity to pinned host, then "
+                    "restore shard + parity from host and reconstruct the lost shard",
+            "value_bytes_per_step": 4 * L,
+            "pct_link_peak": pct(value, LINK_PEAK_GBPS),
+        },
+        "verified": bool(verified),
+        "roofline": {
+            "kernel": "k_gather<8> (parity encode over 8 span tables)" if k == 8 else
+                      f"k_gather<{k}> (parity encode)",
+            "bound": "hbm",
+            "achieved": round(enc_gbps, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(enc_gbps / HBM_PEAK_GBPS, 4),
+            "traffic": None,
+            "bytes_per_launch": (k + 1) * L,
+            "avg_launch_ms": round(enc_ms, 3),
+            "reconstruct_achieved": round(rec_gbps, 1),
+            "reconstruct_avg_launch_ms": round(rec_ms, 3),
+        },
+        "stages": stages,
+        "gemm_proxy": gemm,
+        "cpu_baseline": cpu,
+    }
+    reft.reft_plan_destroy(plan)
+    reft.reft_plan_destroy(pplan)
+    print(json.dumps(record), flush=True)
+    return 0 if verified else 1
+
+
+def cpu_baseline(wl, shards, own, lost, sample_bytes):
+    """The oracle, as it stands, on the first spans of every shard (about ``sample_bytes`` each):
+    pack the own shard, encode the parity, unpack the own shard, reconstruct and unpack the lost
+    one.  Same numerator as the GPU figure (4 x sample stream bytes per pass)."""
+    import numpy as np
+
+    import oracle
+
+    k = wl.k
+    acc, nsp = 0, 0
+    for s in wl.spans:
+        if acc >= sample_bytes:
+            break
+        acc += s.nbytes
+        nsp += 1
+    Ls = acc
+    sizes = [s.nbytes for s in wl.spans[:nsp]]
+    cpu = [[oracle.as_bytes(t.cpu()) for t in sh[:nsp]] for sh in shards]
+    buckets, left = [], Ls
+    bsz = max(wl.bucket_nbytes)
+    while left:
+        buckets.append(min(left, bsz))
+        left -= buckets[-1]
+
+    def one_pass():
+        t0 = time.perf_counter()
+        streams = [oracle.pack_bucketed(cpu[own], buckets)]
+        others = [oracle.pack(cpu[s]) for s in range(k) if s != own]   # peers' packed shards
+        t_peers = time.perf_counter()
+        all_streams = others[:own] + streams + others[own:]
+        par = oracle.encode(all_streams)
+        back = oracle.unpack(streams[0], sizes)
+        rec = oracle.reconstruct([all_streams[s] for s in range(k) if s != lost], par)
+        back_lost = oracle.unpack(rec, sizes)
+        t1 = time.perf_counter()
+        ok = all(np.array_equal(a, b) for a, b in zip(back_lost, cpu[lost])) and \
+            all(np.array_equal(a, b) for a, b in zip(back, cpu[own]))
+        return t1 - t0, ok
+
+    out = {}
+    threads_all = oracle.max_threads()
+    for threads in (1, threads_all):
+        oracle.set_threads(threads)
+        t, ok = one_pass()
+        out[threads] = (t, ok)
+    oracle.set_threads(1)
+    t_all, ok_all = out[threads_all]
+    t_one, ok_one = out[1]
+    return {
+        "value": round(4 * Ls / t_all / 1e9, 3),
+        "unit": "GB/s",
+        "cores": threads_all,
+        "kind": "oracle",
+        "sample": f"first {nsp} spans of each of the {k} shards ({Ls} bytes per shard); one pass = "
+                  f"pack own + pack peers + encode + unpack + reconstruct + unpack, {t_all:.2f} s",
+        "single_thread_value": round(4 * Ls / t_one / 1e9, 3),
+        "single_thread_seconds": round(t_one, 2),
+        "verified": bool(ok_all and ok_one),
+    }
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -94,18 +94,26 @@ int reft_plan_tile_first_span(const reft_plan *plan, uint64_t t, uint64_t *span)
 int reft_plan_split(const reft_plan *plan, double t_bubble, double t_ss, uint64_t *cut);
 
 /* ---- S1 + S2 + S3: bucketed snapshot of one shard into pinned host memory -----------------------
- * For each bucket in order: a gather kernel on pack_stream copies the bucket's bytes from the
- * ragged span tensors into a slot of the staging ring; a hipMemcpyAsync on copy_stream moves the
- * slot to host_dst + B_b.  Events order slot reuse; with >= 2 slots gather and copy overlap.
- * After the last copy a completion event is recorded (see reft_snapshot_wait): the snapshot is
+ * Bucket by bucket, in order, the shard's stream is moved from the ragged span tensors to
+ * host_dst + B_b.  Two transports (tunable "host_path"):
+ *   direct (1, default)  the gather kernel itself stores into the pinned host buffer across the
+ *       host link; one launch per bucket on pack_stream, capped at "link_wgs" workgroups (a few
+ *       dozen saturate the link and leave the rest of the GPU to training).  staging and
+ *       copy_stream are not used and may be NULL.  host_dst must be device-accessible pinned
+ *       memory (hipHostMalloc), else REFT_EINVAL.
+ *   staged (0)  a gather kernel on pack_stream copies each bucket into a slot of the staging ring
+ *       and a hipMemcpyAsync on copy_stream moves the slot to the host.  The ring's slots form
+ *       two groups used alternately, so gathers and copies overlap when staging holds >= 2
+ *       slots; the two streams synchronise through events once per group.
+ * After the last bucket a completion event is recorded (see reft_snapshot_wait): the snapshot is
  * complete only when every bucket has landed (section 4.4: COMPLETED when all tensors are
  * snapshotted).  Postcondition: host_dst[0..L) == stream; host_dst[L..) untouched.
  *
  * span_ptrs[T]   host array of device pointers (may be NULL where the span has 0 bytes).
- * staging        device buffer of staging_bytes >= reft_plan_staging_slot_bytes(plan); up to 4
- *                slots are used.  Its contents are scratch.
- * host_dst       host buffer of host_cap >= L bytes; should be pinned (hipHostMalloc) for the
- *                copy to be asynchronous and fast.
+ * staging        staged path only: 256-byte-aligned device buffer of staging_bytes >=
+ *                reft_plan_staging_slot_bytes(plan); up to 64 slots are used.  Scratch contents;
+ *                must not be shared with another call that may be in flight.
+ * host_dst       host buffer of host_cap >= L bytes, pinned.
  * Errors: REFT_EINVAL, REFT_ESIZE (host_cap < L, staging smaller than one slot), REFT_EHIP.
  */
 int reft_snapshot_pack(reft_plan *plan, const void *const *span_ptrs,
@@ -154,10 +162,29 @@ int reft_parity_encode(reft_plan *plan, const void *const *shard_span_ptrs, uint
 int reft_reconstruct(const void *const *shards, uint32_t k, const void *parity, uint64_t L,
                      void *out_dev, uint32_t *lost_index, reft_stream stream);
 
+/* ---- S6 + S7 in one pass: decode the lost shard directly into its tensors -------------------------
+ * Same result as reft_reconstruct followed by reft_unpack_device, without packed copies of the
+ * survivors: the k-1 surviving shards are read in place through their span pointers, the parity
+ * as a contiguous stream, and the decoded bytes go straight into out_span_ptrs (Eq. 2 applied
+ * span by span; section 4.3, step 3).
+ *
+ * shard_span_ptrs  host array of k*T device pointers, row-major as for reft_parity_encode; row
+ *                  `lost` is ignored (its entries may be NULL).
+ * lost             index of the lost shard, < k;  1 <= k <= REFT_MAX_K - 1.
+ * parity_dev       device pointer to the L parity bytes.
+ * out_span_ptrs    host array of T device pointers: the tensors that receive the lost shard.
+ * Errors: REFT_EINVAL (k or lost out of range, null pointers), REFT_EHIP.
+ */
+int reft_reconstruct_spans(reft_plan *plan, const void *const *shard_span_ptrs, uint32_t k,
+                           uint32_t lost, const void *parity_dev, void *const *out_span_ptrs,
+                           reft_stream stream);
+
 /* ---- S5 + S7: load a shard from pinned host memory back into its tensors (section 4.3, step 1) ---
- * For each bucket: hipMemcpyAsync host_src + B_b -> staging slot on copy_stream, then a scatter
- * kernel on unpack_stream writes the slot's bytes into the span tensors.
- * host_bytes must equal L (REFT_ESIZE).  Other arguments as for reft_snapshot_pack.
+ * The inverse of reft_snapshot_pack, with the same two transports: direct (the scatter kernel
+ * reads the pinned host snapshot across the link, per bucket, on unpack_stream) or staged
+ * (hipMemcpyAsync host_src + B_b -> staging slot on copy_stream, then a scatter kernel on
+ * unpack_stream).  host_bytes must equal L (REFT_ESIZE).  Other arguments as for
+ * reft_snapshot_pack.
  */
 int reft_restore(reft_plan *plan, const void *host_src, uint64_t host_bytes,
                  void *staging, uint64_t staging_bytes,
@@ -166,12 +193,15 @@ int reft_restore_wait(reft_plan *plan);
 
 /* ---- tuning and diagnostics -----------------------------------------------------------------------
  * Process-wide launch parameters, read at each launch:
- *   "max_wgs"      cap on workgroups per kernel launch (0 = 8 per compute unit).  A small cap keeps
+ *   "max_wgs"      cap on workgroups per kernel launch (0 = 16 per compute unit).  A small cap keeps
  *                  a snapshot kernel on few compute units while training kernels run beside it.
  *   "nontemporal"  1 = streaming (non-temporal) loads and stores in the kernels, 0 = plain.
  *   "unroll"       16-byte chunks in flight per thread and source: 1, 2 or 4.
+ *   "host_path"    1 = snapshot/restore kernels access pinned host memory directly (default),
+ *                  0 = staging ring + hipMemcpyAsync.
+ *   "link_wgs"     cap on workgroups of kernels bound by the host link (default 32).
  * Read when a plan is created:
- *   "tile_shift"   log2 of the tile size in bytes, 12..24 (default 16 = 64 KiB).
+ *   "tile_shift"   log2 of the tile size in bytes, 12..24 (default 18 = 256 KiB).
  *   "host_only_plans"  1 = reft_plan_create builds only the host-side sizing (no GPU needed);
  *                  such a plan answers the reft_plan_* queries and is refused (REFT_EINVAL) by
  *                  every call that would touch the GPU.

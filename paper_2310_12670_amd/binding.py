@@ -21,7 +21,7 @@ __all__ = [
     "reft_plan_tile_first_span",
     "reft_snapshot_pack", "reft_snapshot_wait", "reft_snapshot_query",
     "reft_pack_device", "reft_unpack_device", "reft_parity_encode", "reft_reconstruct",
-    "reft_restore", "reft_restore_wait",
+    "reft_reconstruct_spans", "reft_restore", "reft_restore_wait",
     "reft_set_tunable", "reft_get_tunable", "reft_last_error", "reft_version",
 ]
 
@@ -75,6 +75,7 @@ def _load():
         "reft_unpack_device": (i, [vp, vp, u64, vp, vp]),
         "reft_parity_encode": (i, [vp, vp, u32, vp, vp]),
         "reft_reconstruct": (i, [vp, u32, vp, u64, vp, ctypes.POINTER(u32), vp]),
+        "reft_reconstruct_spans": (i, [vp, vp, u32, u32, vp, vp, vp]),
         "reft_restore": (i, [vp, vp, u64, vp, u64, vp, vp, vp]),
         "reft_restore_wait": (i, [vp]),
         "reft_set_tunable": (i, [ctypes.c_char_p, u64]),
@@ -249,6 +250,13 @@ def reft_reconstruct(shards, parity, L: int, out_dev, stream=None) -> int:
     _check(_load().reft_reconstruct(ptr_array(shards), len(shards), _addr(parity), int(L),
                                     _addr(out_dev), ctypes.byref(lost), _stream(stream)))
     return lost.value
+
+
+def reft_reconstruct_spans(plan, shard_span_ptrs, k: int, lost: int, parity_dev, out_span_ptrs,
+                           stream=None) -> None:
+    _check(_load().reft_reconstruct_spans(plan, ptr_array(shard_span_ptrs), int(k), int(lost),
+                                          _addr(parity_dev), ptr_array(out_span_ptrs),
+                                          _stream(stream)))
 
 
 def reft_restore(plan, host_src, staging, span_ptrs, copy_stream=None, unpack_stream=None,

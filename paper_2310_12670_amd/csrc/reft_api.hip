@@ -35,11 +35,13 @@ static int fail(int code, const char *fmt, ...)
                         __FILE__, __LINE__);                                                      \
     } while (0)
 
-static std::atomic<uint64_t> g_max_wgs{0};       // 0 = 8 per compute unit
+static std::atomic<uint64_t> g_max_wgs{0};       // 0 = 16 per compute unit
 static std::atomic<uint64_t> g_nontemporal{1};
 static std::atomic<uint64_t> g_unroll{4};
-static std::atomic<uint64_t> g_tile_shift{16};   // read at plan creation
+static std::atomic<uint64_t> g_tile_shift{18};   // read at plan creation
 static std::atomic<uint64_t> g_host_only{0};     // read at plan creation: no device tables
+static std::atomic<uint64_t> g_host_path{1};     // 1 = kernels access pinned host memory directly
+static std::atomic<uint64_t> g_link_wgs{32};     // grid cap of kernels bound by the host link
 
 extern "C" int reft_set_tunable(const char *name, uint64_t value)
 {
@@ -57,6 +59,12 @@ extern "C" int reft_set_tunable(const char *name, uint64_t value)
     } else if (!strcmp(name, "tile_shift")) {
         if (value < 12 || value > 24) return fail(REFT_EINVAL, "tile_shift must be in [12, 24]");
         g_tile_shift = value;
+    } else if (!strcmp(name, "host_path")) {
+        if (value > 1) return fail(REFT_EINVAL, "host_path must be 0 (staged DMA) or 1 (direct)");
+        g_host_path = value;
+    } else if (!strcmp(name, "link_wgs")) {
+        if (value < 1 || value > (1u << 20)) return fail(REFT_EINVAL, "link_wgs out of range");
+        g_link_wgs = value;
     } else if (!strcmp(name, "host_only_plans")) {
         if (value > 1) return fail(REFT_EINVAL, "host_only_plans must be 0 or 1");
         g_host_only = value;
@@ -74,6 +82,8 @@ extern "C" int reft_get_tunable(const char *name, uint64_t *value)
     else if (!strcmp(name, "unroll")) *value = g_unroll;
     else if (!strcmp(name, "tile_shift")) *value = g_tile_shift;
     else if (!strcmp(name, "host_only_plans")) *value = g_host_only;
+    else if (!strcmp(name, "host_path")) *value = g_host_path;
+    else if (!strcmp(name, "link_wgs")) *value = g_link_wgs;
     else return fail(REFT_EINVAL, "unknown tunable '%s'", name);
     return REFT_OK;
 }
@@ -86,7 +96,8 @@ extern "C" const char *reft_version(void) { return "libreft 0.1 (gfx950)"; }
 // ------------------------------------------------------------------------------------------------
 namespace {
 constexpr int kRing = 4;        // pointer-table uploads that may be in flight at once
-constexpr int kMaxSlots = 4;    // staging slots used by the bucket pipelines
+constexpr int kMaxSlots = 64;   // staging slots used by the staged bucket pipelines
+constexpr int kGroups = 2;      // the slots form two groups that alternate (double buffering)
 
 struct Event {
     hipEvent_t ev = nullptr;
@@ -113,8 +124,8 @@ struct reft_plan {
     Event ring_ev[kRing];
     unsigned ring_next = 0;
     // bucket pipelines
-    Event pack_filled[kMaxSlots], pack_free[kMaxSlots], pack_done;
-    Event rest_filled[kMaxSlots], rest_free[kMaxSlots], rest_done;
+    Event pack_filled[kGroups], pack_free[kGroups], pack_done;
+    Event rest_filled[kGroups], rest_free[kGroups], rest_done;
 
     PlanTables tables() const { return PlanTables{d_off, d_first, T, L, tile_shift}; }
 };
@@ -122,8 +133,29 @@ struct reft_plan {
 static LaunchCfg launch_cfg(const reft_plan *p)
 {
     uint64_t w = g_max_wgs;
-    if (w == 0) w = 8ull * (uint64_t)(p ? p->num_cus : 256);
+    if (w == 0) w = 16ull * (uint64_t)(p ? p->num_cus : 256);
     return LaunchCfg{(uint32_t)w, (uint32_t)g_unroll.load(), g_nontemporal.load() != 0};
+}
+
+// Kernels whose rate is set by the host link need only a few workgroups to saturate it.
+static LaunchCfg link_cfg(const reft_plan *p)
+{
+    LaunchCfg c = launch_cfg(p);
+    const uint64_t w = g_link_wgs.load();
+    if (w < c.max_wgs) c.max_wgs = (uint32_t)w;
+    return c;
+}
+
+// The address at which the GPU sees a host buffer, or 0 if it is not mapped for device access
+// (pageable memory).  Clears the sticky error a failed lookup leaves behind.
+static uint64_t device_view_of_host(const void *host)
+{
+    void *d = nullptr;
+    if (hipHostGetDevicePointer(&d, const_cast<void *>(host), 0) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return (uint64_t)(uintptr_t)d;
 }
 
 static int make_event(Event &e)
@@ -299,7 +331,7 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
     int rc;
     for (int i = 0; i < kRing; ++i)
         if ((rc = make_event(p->ring_ev[i]))) return rc;
-    for (int i = 0; i < kMaxSlots; ++i) {
+    for (int i = 0; i < kGroups; ++i) {
         if ((rc = make_event(p->pack_filled[i])) || (rc = make_event(p->pack_free[i])) ||
             (rc = make_event(p->rest_filled[i])) || (rc = make_event(p->rest_free[i])))
             return rc;
@@ -324,7 +356,7 @@ extern "C" void reft_plan_destroy(reft_plan *p)
         }
     };
     for (int i = 0; i < kRing; ++i) drain(p->ring_ev[i]);
-    for (int i = 0; i < kMaxSlots; ++i) {
+    for (int i = 0; i < kGroups; ++i) {
         drain(p->pack_filled[i]);
         drain(p->pack_free[i]);
         drain(p->rest_filled[i]);
@@ -432,28 +464,59 @@ extern "C" int reft_snapshot_pack(reft_plan *p, const void *const *span_ptrs, vo
         return fail(REFT_ESIZE, "reft_snapshot_pack: host buffer holds %llu bytes, stream has %llu",
                     (unsigned long long)host_cap, (unsigned long long)p->L);
     if (p->L && !host_dst) return fail(REFT_EINVAL, "reft_snapshot_pack: null host buffer");
-    int nslots = 1;
-    if ((rc = staging_slots(p, staging, staging_bytes, "reft_snapshot_pack", &nslots))) return rc;
     hipStream_t ps = (hipStream_t)pack_stream, cs = (hipStream_t)copy_stream;
-
+    const PlanTables pt = p->tables();
     const uint64_t *tab = nullptr;
     int entry = 0;
+
+    if (g_host_path.load() == 1) {
+        // Direct path: the gather kernel stores straight into the pinned host buffer over the
+        // host link, one launch per bucket, in order on pack_stream.  No staging, no DMA.
+        const uint64_t hview = p->L ? device_view_of_host(host_dst) : 0;
+        if (p->L && !hview)
+            return fail(REFT_EINVAL, "reft_snapshot_pack: host buffer is not mapped for device "
+                                     "access (not pinned); set tunable host_path=0 to stage it");
+        if ((rc = upload_ptrs(p, span_ptrs, 1, ps, &tab, &entry))) return rc;
+        const LaunchCfg cfg = link_cfg(p);
+        for (uint64_t b = 0; b < p->NB; ++b)
+            HIPCHK(launch_gather(pt, tab, 1, false, nullptr, hview, p->bstart[b], p->bstart[b + 1],
+                                 cfg, ps));
+        if ((rc = record(p->ring_ev[entry], ps))) return rc;
+        return record(p->pack_done, ps);
+    }
+
+    // Staged path: gather kernels fill staging slots, hipMemcpyAsync moves each bucket to the
+    // host.  The slots form two groups that alternate between the streams; the streams meet only
+    // once per group (cross-stream events are costly when thousands are in flight).
+    int nslots = 1;
+    if ((rc = staging_slots(p, staging, staging_bytes, "reft_snapshot_pack", &nslots))) return rc;
     if ((rc = upload_ptrs(p, span_ptrs, 1, ps, &tab, &entry))) return rc;
     const LaunchCfg cfg = launch_cfg(p);
-    const PlanTables pt = p->tables();
     const uint64_t stride = slot_stride(p);
-    for (uint64_t b = 0; b < p->NB; ++b) {
-        const int slot = (int)(b % (uint64_t)nslots);
-        const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
-        const uint64_t slot_addr = (uint64_t)(uintptr_t)staging + (uint64_t)slot * stride + (lo & 255);
-        // the slot's previous occupant must have left for the host
-        if ((rc = wait_on(ps, p->pack_free[slot]))) return rc;
-        HIPCHK(launch_gather(pt, tab, 1, false, slot_addr - lo, lo, hi, cfg, ps));
-        if ((rc = record(p->pack_filled[slot], ps))) return rc;
-        if ((rc = wait_on(cs, p->pack_filled[slot]))) return rc;
-        HIPCHK(hipMemcpyAsync((uint8_t *)host_dst + lo, (const void *)(uintptr_t)slot_addr, hi - lo,
-                              hipMemcpyDeviceToHost, cs));
-        if ((rc = record(p->pack_free[slot], cs))) return rc;
+    const int ngroups = nslots >= kGroups ? kGroups : 1;
+    const uint64_t per_group = (uint64_t)(nslots / ngroups);
+    uint64_t batch = 0;
+    for (uint64_t b0 = 0; b0 < p->NB; b0 += per_group, ++batch) {
+        const int g = (int)(batch % (uint64_t)ngroups);
+        const uint64_t b1 = b0 + per_group < p->NB ? b0 + per_group : p->NB;
+        // the group's previous occupants must have left for the host
+        if ((rc = wait_on(ps, p->pack_free[g]))) return rc;
+        for (uint64_t b = b0; b < b1; ++b) {
+            const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
+            const uint64_t slot = (uint64_t)g * per_group + (b - b0);
+            const uint64_t slot_addr = (uint64_t)(uintptr_t)staging + slot * stride + (lo & 255);
+            HIPCHK(launch_gather(pt, tab, 1, false, nullptr, slot_addr - lo, lo, hi, cfg, ps));
+        }
+        if ((rc = record(p->pack_filled[g], ps))) return rc;
+        if ((rc = wait_on(cs, p->pack_filled[g]))) return rc;
+        for (uint64_t b = b0; b < b1; ++b) {
+            const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
+            const uint64_t slot = (uint64_t)g * per_group + (b - b0);
+            const uint64_t slot_addr = (uint64_t)(uintptr_t)staging + slot * stride + (lo & 255);
+            HIPCHK(hipMemcpyAsync((uint8_t *)host_dst + lo, (const void *)(uintptr_t)slot_addr,
+                                  hi - lo, hipMemcpyDeviceToHost, cs));
+        }
+        if ((rc = record(p->pack_free[g], cs))) return rc;
     }
     if ((rc = record(p->ring_ev[entry], ps))) return rc;
     // completion: all buckets have landed once copy_stream reaches this point
@@ -496,7 +559,7 @@ extern "C" int reft_pack_device(reft_plan *p, const void *const *span_ptrs, void
     const uint64_t *tab = nullptr;
     int entry = 0;
     if ((rc = upload_ptrs(p, span_ptrs, 1, s, &tab, &entry))) return rc;
-    HIPCHK(launch_gather(p->tables(), tab, 1, false, (uint64_t)(uintptr_t)dst_dev, 0, p->L,
+    HIPCHK(launch_gather(p->tables(), tab, 1, false, nullptr, (uint64_t)(uintptr_t)dst_dev, 0, p->L,
                          launch_cfg(p), s));
     return record(p->ring_ev[entry], s);
 }
@@ -547,7 +610,7 @@ extern "C" int reft_parity_encode(reft_plan *p, const void *const *shard_span_pt
         uint32_t rows = k - done;
         const uint32_t cap = (uint32_t)kMaxSrc - (acc ? 1u : 0u);
         if (rows > cap) rows = cap;
-        HIPCHK(launch_gather(pt, tab + (uint64_t)done * p->T, (int)rows, acc,
+        HIPCHK(launch_gather(pt, tab + (uint64_t)done * p->T, (int)rows, acc, nullptr,
                              (uint64_t)(uintptr_t)parity_dev, 0, p->L, cfg, s));
         done += rows;
     }
@@ -599,6 +662,56 @@ extern "C" int reft_reconstruct(const void *const *shards, uint32_t k, const voi
     return REFT_OK;
 }
 
+// S6 + S7 in one pass: survivors read in place through their span tables, the parity as a
+// contiguous stream, the result written straight into the lost shard's tensors.
+extern "C" int reft_reconstruct_spans(reft_plan *p, const void *const *shard_span_ptrs, uint32_t k,
+                                      uint32_t lost, const void *parity_dev,
+                                      void *const *out_span_ptrs, reft_stream stream)
+{
+    int rc = check_plan(p, "reft_reconstruct_spans");
+    if (rc) return rc;
+    if (k < 1 || k > REFT_MAX_K - 1)
+        return fail(REFT_EINVAL, "reft_reconstruct_spans: k = %u outside [1, %d]", k,
+                    REFT_MAX_K - 1);
+    if (lost >= k) return fail(REFT_EINVAL, "reft_reconstruct_spans: lost = %u but k = %u", lost, k);
+    if (!shard_span_ptrs) return fail(REFT_EINVAL, "reft_reconstruct_spans: null pointer array");
+    if ((rc = check_span_ptrs(p, out_span_ptrs, 1, "reft_reconstruct_spans(out)"))) return rc;
+    // rows: the k-1 survivors, then the parity expressed as a span row, then the destination
+    const uint64_t T = p->T;
+    std::vector<const void *> rows((size_t)(k + 1) * T);
+    uint32_t r = 0;
+    for (uint32_t s = 0; s < k; ++s) {
+        if (s == lost) continue;
+        if ((rc = check_span_ptrs(p, shard_span_ptrs + (size_t)s * T, 1, "reft_reconstruct_spans")))
+            return rc;
+        for (uint64_t t = 0; t < T; ++t) rows[(size_t)r * T + t] = shard_span_ptrs[(size_t)s * T + t];
+        ++r;
+    }
+    if (p->L == 0) return REFT_OK;
+    if (!parity_dev) return fail(REFT_EINVAL, "reft_reconstruct_spans: null parity");
+    for (uint64_t t = 0; t < T; ++t)
+        rows[(size_t)r * T + t] = (const uint8_t *)parity_dev + p->off[t];
+    ++r;                                                       // r == k source rows
+    for (uint64_t t = 0; t < T; ++t) rows[(size_t)r * T + t] = out_span_ptrs[t];
+    hipStream_t s = (hipStream_t)stream;
+    const uint64_t *tab = nullptr;
+    int entry = 0;
+    if ((rc = upload_ptrs(p, rows.data(), k + 1, s, &tab, &entry))) return rc;
+    const uint64_t *dtab = tab + (uint64_t)k * T;
+    const LaunchCfg cfg = launch_cfg(p);
+    const PlanTables pt = p->tables();
+    uint32_t done = 0;
+    while (done < k) {
+        const bool acc = done > 0;
+        uint32_t n = k - done;
+        const uint32_t cap = (uint32_t)kMaxSrc - (acc ? 1u : 0u);
+        if (n > cap) n = cap;
+        HIPCHK(launch_gather(pt, tab + (uint64_t)done * T, (int)n, acc, dtab, 0, 0, p->L, cfg, s));
+        done += n;
+    }
+    return record(p->ring_ev[entry], s);
+}
+
 // ------------------------------------------------------------------------------------------------
 // S5 + S7: restore
 // ------------------------------------------------------------------------------------------------
@@ -613,28 +726,54 @@ extern "C" int reft_restore(reft_plan *p, const void *host_src, uint64_t host_by
         return fail(REFT_ESIZE, "reft_restore: host snapshot has %llu bytes, stream has %llu",
                     (unsigned long long)host_bytes, (unsigned long long)p->L);
     if (p->L && !host_src) return fail(REFT_EINVAL, "reft_restore: null host buffer");
-    int nslots = 1;
-    if ((rc = staging_slots(p, staging, staging_bytes, "reft_restore", &nslots))) return rc;
     hipStream_t cs = (hipStream_t)copy_stream, us = (hipStream_t)unpack_stream;
-
+    const PlanTables pt = p->tables();
     const uint64_t *tab = nullptr;
     int entry = 0;
+
+    if (g_host_path.load() == 1) {
+        // Direct path: the scatter kernel loads the snapshot from pinned host memory itself.
+        const uint64_t hview = p->L ? device_view_of_host(host_src) : 0;
+        if (p->L && !hview)
+            return fail(REFT_EINVAL, "reft_restore: host buffer is not mapped for device access "
+                                     "(not pinned); set tunable host_path=0 to stage it");
+        if ((rc = upload_ptrs(p, span_ptrs, 1, us, &tab, &entry))) return rc;
+        const LaunchCfg cfg = link_cfg(p);
+        for (uint64_t b = 0; b < p->NB; ++b)
+            HIPCHK(launch_scatter(pt, tab, hview, p->bstart[b], p->bstart[b + 1], cfg, us));
+        if ((rc = record(p->ring_ev[entry], us))) return rc;
+        return record(p->rest_done, us);
+    }
+
+    int nslots = 1;
+    if ((rc = staging_slots(p, staging, staging_bytes, "reft_restore", &nslots))) return rc;
     if ((rc = upload_ptrs(p, span_ptrs, 1, us, &tab, &entry))) return rc;
     const LaunchCfg cfg = launch_cfg(p);
-    const PlanTables pt = p->tables();
     const uint64_t stride = slot_stride(p);
-    for (uint64_t b = 0; b < p->NB; ++b) {
-        const int slot = (int)(b % (uint64_t)nslots);
-        const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
-        const uint64_t slot_addr = (uint64_t)(uintptr_t)staging + (uint64_t)slot * stride + (lo & 255);
-        // the slot's previous occupant must have been scattered
-        if ((rc = wait_on(cs, p->rest_free[slot]))) return rc;
-        HIPCHK(hipMemcpyAsync((void *)(uintptr_t)slot_addr, (const uint8_t *)host_src + lo, hi - lo,
-                              hipMemcpyHostToDevice, cs));
-        if ((rc = record(p->rest_filled[slot], cs))) return rc;
-        if ((rc = wait_on(us, p->rest_filled[slot]))) return rc;
-        HIPCHK(launch_scatter(pt, tab, slot_addr - lo, lo, hi, cfg, us));
-        if ((rc = record(p->rest_free[slot], us))) return rc;
+    const int ngroups = nslots >= kGroups ? kGroups : 1;
+    const uint64_t per_group = (uint64_t)(nslots / ngroups);
+    uint64_t batch = 0;
+    for (uint64_t b0 = 0; b0 < p->NB; b0 += per_group, ++batch) {
+        const int g = (int)(batch % (uint64_t)ngroups);
+        const uint64_t b1 = b0 + per_group < p->NB ? b0 + per_group : p->NB;
+        // the group's previous occupants must have been scattered
+        if ((rc = wait_on(cs, p->rest_free[g]))) return rc;
+        for (uint64_t b = b0; b < b1; ++b) {
+            const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
+            const uint64_t slot = (uint64_t)g * per_group + (b - b0);
+            const uint64_t slot_addr = (uint64_t)(uintptr_t)staging + slot * stride + (lo & 255);
+            HIPCHK(hipMemcpyAsync((void *)(uintptr_t)slot_addr, (const uint8_t *)host_src + lo,
+                                  hi - lo, hipMemcpyHostToDevice, cs));
+        }
+        if ((rc = record(p->rest_filled[g], cs))) return rc;
+        if ((rc = wait_on(us, p->rest_filled[g]))) return rc;
+        for (uint64_t b = b0; b < b1; ++b) {
+            const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
+            const uint64_t slot = (uint64_t)g * per_group + (b - b0);
+            const uint64_t slot_addr = (uint64_t)(uintptr_t)staging + slot * stride + (lo & 255);
+            HIPCHK(launch_scatter(pt, tab, slot_addr - lo, lo, hi, cfg, us));
+        }
+        if ((rc = record(p->rest_free[g], us))) return rc;
     }
     if ((rc = record(p->ring_ev[entry], us))) return rc;
     return record(p->rest_done, us);

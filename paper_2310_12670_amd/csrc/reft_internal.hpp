@@ -29,12 +29,13 @@ struct SrcBases {
     uint64_t p[kMaxSrc];
 };
 
-// dst_vbase + o is the destination address of stream byte o, for o in [lo, hi).
+// The destination address of stream byte o, for o in [lo, hi), is dst_vbase + o, or, when dtab
+// (one row of T span pointers) is not null, the byte's place in the destination's own span.
 // tab holds nrows rows of T span pointers (row stride T); the kernel XORs the rows' streams and,
 // if acc, the destination's current contents.  nrows + acc <= kMaxSrc.
 hipError_t launch_gather(const PlanTables &pt, const uint64_t *tab, int nrows, bool acc,
-                         uint64_t dst_vbase, uint64_t lo, uint64_t hi, const LaunchCfg &cfg,
-                         hipStream_t stream);
+                         const uint64_t *dtab, uint64_t dst_vbase, uint64_t lo, uint64_t hi,
+                         const LaunchCfg &cfg, hipStream_t stream);
 
 // src_vbase + o is the source address of stream byte o; tab is one row of T span pointers.
 hipError_t launch_scatter(const PlanTables &pt, const uint64_t *tab, uint64_t src_vbase,

@@ -148,12 +148,14 @@ __device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], ui
     }
 }
 
-// dst_vbase + o  <-  XOR over rows j < K of (tab[j*T + span(o)] + offset of o in its span);
-// with acc != 0 only K-1 rows are read and the destination itself is the K-th source.
+// destination of stream byte o  <-  XOR over rows j < K of (tab[j*T + span(o)] + offset of o in
+// its span).  The destination is dst_vbase + o, or, if dtab is not null, ragged as well:
+// dtab[span(o)] + offset.  With acc != 0 only K-1 rows are read and the destination itself is the
+// K-th source.
 template <int K, int U, bool NT>
 __global__ void __launch_bounds__(kThreads)
-k_gather(PlanTables pt, const uint64_t *__restrict__ tab, uint64_t dst_vbase, uint64_t lo,
-         uint64_t hi, uint32_t acc)
+k_gather(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *__restrict__ dtab,
+         uint64_t dst_vbase, uint64_t lo, uint64_t hi, uint32_t acc)
 {
     const uint32_t sh = pt.tile_shift;
     const uint64_t t_last = (hi - 1) >> sh;
@@ -169,13 +171,14 @@ k_gather(PlanTables pt, const uint64_t *__restrict__ tab, uint64_t dst_vbase, ui
             const uint64_t so = pt.off[i];
             uint64_t pe = pt.off[i + 1];
             if (pe > e) pe = e;
+            const uint64_t d = dtab ? dtab[i] + (o - so) : dst_vbase + o;
             uint64_t s[K];
 #pragma unroll
             for (int j = 0; j < K - 1; ++j) s[j] = tab[(uint64_t)j * pt.T + i] + (o - so);
             // accumulate mode: the destination's current bytes are the last source (each byte
             // is read and then written by the same thread, so in-place is safe)
-            s[K - 1] = acc ? dst_vbase + o : tab[(uint64_t)(K - 1) * pt.T + i] + (o - so);
-            xor_piece<K, U, NT>(dst_vbase + o, s, (uint32_t)(pe - o));
+            s[K - 1] = acc ? d : tab[(uint64_t)(K - 1) * pt.T + i] + (o - so);
+            xor_piece<K, U, NT>(d, s, (uint32_t)(pe - o));
             o = pe;
         }
     }
@@ -254,16 +257,17 @@ static uint32_t grid_for(uint64_t ntiles, const LaunchCfg &cfg)
     }
 
 hipError_t launch_gather(const PlanTables &pt, const uint64_t *tab, int nrows, bool acc,
-                         uint64_t dst_vbase, uint64_t lo, uint64_t hi, const LaunchCfg &cfg,
-                         hipStream_t stream)
+                         const uint64_t *dtab, uint64_t dst_vbase, uint64_t lo, uint64_t hi,
+                         const LaunchCfg &cfg, hipStream_t stream)
 {
     if (lo >= hi) return hipSuccess;
     if (hi > pt.L) return hipErrorInvalidValue;
-    void (*fn)(PlanTables, const uint64_t *, uint64_t, uint64_t, uint64_t, uint32_t) = nullptr;
+    void (*fn)(PlanTables, const uint64_t *, const uint64_t *, uint64_t, uint64_t, uint64_t,
+               uint32_t) = nullptr;
     const int nsrc = nrows + (acc ? 1 : 0);
     REFT_PICK_K(k_gather, fn, nsrc)
     const uint64_t ntiles = ((hi - 1) >> pt.tile_shift) - (lo >> pt.tile_shift) + 1;
-    hipLaunchKernelGGL(fn, dim3(grid_for(ntiles, cfg)), dim3(kThreads), 0, stream, pt, tab,
+    hipLaunchKernelGGL(fn, dim3(grid_for(ntiles, cfg)), dim3(kThreads), 0, stream, pt, tab, dtab,
                        dst_vbase, lo, hi, acc ? 1u : 0u);
     return hipGetLastError();
 }

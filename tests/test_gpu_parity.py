@@ -28,9 +28,12 @@ def dev():
     return d
 
 
-@pytest.fixture(autouse=True)
-def default_tunables():
-    saved = {n: reft.reft_get_tunable(n) for n in ("max_wgs", "nontemporal", "unroll", "tile_shift")}
+@pytest.fixture(autouse=True, params=["direct", "staged"])
+def default_tunables(request):
+    """Every case runs with both host transports; launch parameters are restored afterwards."""
+    names = ("max_wgs", "nontemporal", "unroll", "tile_shift", "host_path", "link_wgs")
+    saved = {n: reft.reft_get_tunable(n) for n in names}
+    reft.reft_set_tunable("host_path", 1 if request.param == "direct" else 0)
     yield
     for n, v in saved.items():
         reft.reft_set_tunable(n, v)
@@ -137,10 +140,21 @@ def run_case(dev, shards, sizes, buckets=None, uniform=0, lost=None, nslots=2, o
             assert np.array_equal(want, streams[j])
             out.check("reconstruct")
 
-        # S5+S7: restore shard 0 from the host snapshot into fresh tensors
         gen = torch.Generator(device=dev)
         gen.manual_seed(1000 + seed)
         phases = fresh_phases if fresh_phases is not None else [0] * T
+
+        # S6+S7 fused: decode the lost shard straight into fresh tensors, survivors read in place
+        for j in ([k - 1] if lost is None else [lost]):
+            arena0, fresh0 = arena_spans(sizes, phases, dev, gen)
+            rows = [None if s == j else t for s, sh in enumerate(shards) for t in sh]
+            reft.reft_reconstruct_spans(plan, rows, k, j, par.view, fresh0, s1)
+            s1.synchronize()
+            want = oracle.reconstruct([streams[s] for s in range(k) if s != j], parity_ref)
+            for t, (f, w) in enumerate(zip(fresh0, oracle.unpack(want, sizes))):
+                assert np.array_equal(f.cpu().numpy(), w), f"reconstruct_spans lost={j} span {t}"
+
+        # S5+S7: restore shard 0 from the host snapshot into fresh tensors
         arena, fresh = arena_spans(sizes, phases, dev, gen)
         before = arena.cpu().numpy().copy()
         reft.reft_restore(plan, host.view, staging, fresh, s2, s1, host_bytes=L)
@@ -303,6 +317,13 @@ def test_shard_counts_including_chained_passes(dev, k):
         assert np.array_equal(par.bytes(), parity_ref)
         par.check("parity_encode")
         if k <= 31:
+            j = k // 3
+            arena0, fresh0 = arena_spans(sizes, [4, 0, 0, 9], dev, gen)
+            rows = [None if s == j else t for s, sh in enumerate(shards) for t in sh]
+            reft.reft_reconstruct_spans(plan, rows, k, j, par.view, fresh0)
+            torch.cuda.synchronize()
+            for f, w in zip(fresh0, cpu[j]):
+                assert np.array_equal(f.cpu().numpy(), w), ("reconstruct_spans", k)
             packed = []
             for s in range(k):
                 buf = torch.empty(L, dtype=torch.uint8, device=dev)
@@ -342,6 +363,7 @@ def test_float_bit_patterns_survive(dev):
 @pytest.mark.parametrize("nt", [0, 1])
 @pytest.mark.parametrize("max_wgs,tile_shift", [(0, 16), (1, 12), (7, 14), (64, 20)])
 def test_launch_parameters_do_not_change_results(dev, unroll, nt, max_wgs, tile_shift):
+    reft.reft_set_tunable("link_wgs", 3 if max_wgs == 7 else 32)
     reft.reft_set_tunable("unroll", unroll)
     reft.reft_set_tunable("nontemporal", nt)
     reft.reft_set_tunable("max_wgs", max_wgs)
@@ -366,8 +388,13 @@ def test_size_and_argument_errors(dev):
             reft.reft_snapshot_pack(plan, spans, staging, host, host_cap=1023)
         assert e.value.code == reft.REFT_ESIZE
         with pytest.raises(reft.ReftError) as e:      # staging smaller than one slot
+            reft.reft_set_tunable("host_path", 0)
             reft.reft_snapshot_pack(plan, spans, staging, host, staging_bytes=512)
         assert e.value.code == reft.REFT_ESIZE
+        with pytest.raises(reft.ReftError) as e:      # direct path needs pinned host memory
+            reft.reft_set_tunable("host_path", 1)
+            reft.reft_snapshot_pack(plan, spans, staging, np.zeros(2048, np.uint8))
+        assert e.value.code == reft.REFT_EINVAL
         with pytest.raises(reft.ReftError) as e:      # restore of a snapshot of another length
             reft.reft_restore(plan, host, staging, spans, host_bytes=1025)
         assert e.value.code == reft.REFT_ESIZE
