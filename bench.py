@@ -48,6 +48,15 @@ def main() -> int:
                          "(0 = as long as one save phase; negative = skip)")
     ap.add_argument("--snapshot-wgs", type=int, default=0,
                     help="cap on workgroups of the snapshot kernels while the GEMM proxy runs")
+    ap.add_argument("--save-path", choices=["direct", "staged"], default="staged",
+                    help="snapshot transport. staged: staging ring + hipMemcpyAsync on the DMA "
+                         "engines (what runs beside training); direct: the gather kernel stores "
+                         "to pinned host memory itself")
+    ap.add_argument("--load-path", choices=["direct", "staged"], default="direct",
+                    help="restore transport (recovery: the GPU is otherwise idle)")
+    ap.add_argument("--staging-slots", type=int, default=16, help="slots per staging ring")
+    ap.add_argument("--link-wgs", type=int, default=0,
+                    help="cap on workgroups of the link-bound kernels (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-mib", type=int, default=512,
                     help="bytes per shard of the CPU-oracle sample, MiB")
@@ -82,10 +91,15 @@ def main() -> int:
     plan = reft.reft_plan_create(sizes, wl.bucket_nbytes)
     bucket = reft.reft_plan_max_bucket_bytes(plan)
     pplan = reft.reft_plan_create([L], None, bucket)           # the parity as a 1-span shard
-    nslots = 4
-    def ring(p):
-        return torch.empty(nslots * reft.reft_plan_staging_slot_bytes(p), dtype=torch.uint8, device=dev)
-    stag_save, stag_psave, stag_load, stag_pload = ring(plan), ring(pplan), ring(plan), ring(pplan)
+    save_staged = args.save_path == "staged"
+    load_staged = args.load_path == "staged"
+    def ring(p, use):
+        if not use:
+            return None
+        return torch.empty(args.staging_slots * reft.reft_plan_staging_slot_bytes(p),
+                           dtype=torch.uint8, device=dev)
+    stag_save, stag_psave = ring(plan, save_staged), ring(pplan, save_staged)
+    stag_load, stag_pload = ring(plan, load_staged), ring(pplan, load_staged)
     t0 = time.time()
     host_snap = torch.empty(L, dtype=torch.uint8, pin_memory=True)
     host_par = torch.empty(L, dtype=torch.uint8, pin_memory=True)
@@ -103,11 +117,22 @@ def main() -> int:
     p_par = reft.ptr_array([parity])
     p_par2 = reft.ptr_array([parity2])
 
-    s_pack, s_copy, s_xor, s_h2d, s_unpack = (torch.cuda.Stream() for _ in range(5))
+    if args.link_wgs:
+        reft.reft_set_tunable("link_wgs", args.link_wgs)
+    # s_snap / s_load carry the link-bound work (and, staged, the gather / scatter kernels);
+    # s_copy / s_h2d carry the DMA transfers of the staged path; s_xor the HBM-bound XOR kernels.
+    s_snap, s_xor, s_load = (torch.cuda.Stream() for _ in range(3))
+    s_copy = torch.cuda.Stream() if save_staged else s_snap
+    s_h2d = torch.cuda.Stream() if load_staged else s_load
+    snap_done_stream = s_copy
     enc_events, rec_events = [], []
 
     def save_phase(timed):
-        reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_pack, s_copy)
+        """Snapshot of the own shard beside the parity encode, then the parity's snapshot.
+        Returns the event after which the own shard's host copy is complete."""
+        reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_snap, s_copy)
+        own_done = torch.cuda.Event()
+        own_done.record(snap_done_stream)
         if timed:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(s_xor)
@@ -115,14 +140,19 @@ def main() -> int:
         if timed:
             e1.record(s_xor)
             enc_events.append((e0, e1))
-        s_pack.wait_stream(s_xor)
-        reft.reft_snapshot_pack(pplan, p_par, stag_psave, host_par, s_pack, s_copy)
+        s_snap.wait_stream(s_xor)
+        reft.reft_snapshot_pack(pplan, p_par, stag_psave, host_par, s_snap, s_copy)
+        return own_done
 
-    def load_phase(timed):
-        s_h2d.wait_stream(s_copy)                  # the snapshot is complete on the host
-        reft.reft_restore(plan, host_snap, stag_load, p_fresh_own, s_h2d, s_unpack)
-        reft.reft_restore(pplan, host_par, stag_pload, p_par2, s_h2d, s_unpack)
-        s_xor.wait_stream(s_unpack)
+    def load_phase(timed, own_done):
+        """Restore of the own shard (as soon as its snapshot is complete: it shares the link with
+        the parity's snapshot, in the other direction), then the parity, then the decode."""
+        first = s_h2d
+        first.wait_event(own_done)
+        reft.reft_restore(plan, host_snap, stag_load, p_fresh_own, s_h2d, s_load)
+        first.wait_stream(snap_done_stream)             # the parity is complete on the host
+        reft.reft_restore(pplan, host_par, stag_pload, p_par2, s_h2d, s_load)
+        s_xor.wait_stream(s_load)
         if timed:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(s_xor)
@@ -131,12 +161,11 @@ def main() -> int:
             e1.record(s_xor)
             rec_events.append((e0, e1))
         # the next step's save may not overwrite what this step's load still reads
-        s_pack.wait_stream(s_xor)
-        s_copy.wait_stream(s_h2d)
+        s_snap.wait_stream(s_xor)
+        s_snap.wait_stream(s_load)
 
     def step(timed=False):
-        save_phase(timed)
-        load_phase(timed)
+        load_phase(timed, save_phase(timed))
 
     for _ in range(args.warmup):
         step()
@@ -185,14 +214,14 @@ def main() -> int:
     del packed
 
     def snap():
-        reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_pack, s_copy)
-        s_xor.wait_stream(s_copy)
+        s_snap.wait_stream(s_xor)
+        reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_snap, s_copy)
+        s_xor.wait_stream(snap_done_stream)
     def rest():
         s_h2d.wait_stream(s_xor)
-        reft.reft_restore(plan, host_snap, stag_load, p_fresh_own, s_h2d, s_unpack)
-        s_xor.wait_stream(s_unpack)
-    s_pack.wait_stream(s_xor)
-    t_snap = timed_alone(lambda: (s_pack.wait_stream(s_xor), snap()), s_xor, reps=3)
+        reft.reft_restore(plan, host_snap, stag_load, p_fresh_own, s_h2d, s_load)
+        s_xor.wait_stream(s_load)
+    t_snap = timed_alone(snap, s_xor, reps=3)
     t_rest = timed_alone(rest, s_xor, reps=3)
 
     def pct(x, peak):
@@ -239,6 +268,10 @@ def main() -> int:
         save_phase(False)
         torch.cuda.synchronize()
         t_save = time.perf_counter() - ts0
+        ts0 = time.perf_counter()
+        save_phase(False)
+        torch.cuda.synchronize()
+        t_save = min(t_save, time.perf_counter() - ts0)
         span = args.gemm_seconds if args.gemm_seconds > 0 else t_save
         count = max(10, int(span / t_one))
         e0, e1 = gemms(count)
@@ -292,6 +325,9 @@ def main() -> int:
             "step": "snapshot own shard + XOR parity + snapshot parity to pinned host, then "
                     "restore shard + parity from host and reconstruct the lost shard",
             "value_bytes_per_step": 4 * L,
+            "save_path": args.save_path, "load_path": args.load_path,
+            "staging_slots": args.staging_slots,
+            "link_wgs": reft.reft_get_tunable("link_wgs"),
             "pct_link_peak": pct(value, LINK_PEAK_GBPS),
         },
         "verified": bool(verified),

@@ -95,22 +95,26 @@ int reft_plan_split(const reft_plan *plan, double t_bubble, double t_ss, uint64_
 
 /* ---- S1 + S2 + S3: bucketed snapshot of one shard into pinned host memory -----------------------
  * Bucket by bucket, in order, the shard's stream is moved from the ragged span tensors to
- * host_dst + B_b.  Two transports (tunable "host_path"):
- *   direct (1, default)  the gather kernel itself stores into the pinned host buffer across the
- *       host link; one launch per bucket on pack_stream, capped at "link_wgs" workgroups (a few
- *       dozen saturate the link and leave the rest of the GPU to training).  staging and
- *       copy_stream are not used and may be NULL.  host_dst must be device-accessible pinned
- *       memory (hipHostMalloc), else REFT_EINVAL.
- *   staged (0)  a gather kernel on pack_stream copies each bucket into a slot of the staging ring
- *       and a hipMemcpyAsync on copy_stream moves the slot to the host.  The ring's slots form
- *       two groups used alternately, so gathers and copies overlap when staging holds >= 2
- *       slots; the two streams synchronise through events once per group.
+ * host_dst + B_b.  Two transports, chosen per call by the staging argument:
+ *   staged (staging != NULL)  a gather kernel on pack_stream copies each bucket into a slot of the
+ *       staging ring and a hipMemcpyAsync on copy_stream moves the slot to the host on the DMA
+ *       engines, which leaves the compute units and their path to memory to training kernels
+ *       running beside the snapshot.  The ring's slots form two groups used alternately, so
+ *       gathers and copies overlap when staging holds >= 2 slots; the two streams synchronise
+ *       through events once per group.  pack_stream may equal copy_stream (fully in order).
+ *   direct (staging == NULL)  the gather kernel itself stores into the pinned host buffer across
+ *       the host link: one launch per bucket on pack_stream, capped at "link_wgs" workgroups (a
+ *       few dozen saturate the link).  No staging memory, no DMA, no second pass over HBM;
+ *       copy_stream is not used.  Meant for times when the GPU is otherwise idle (pipeline
+ *       bubbles, recovery): kernels that keep the link's write path full slow down kernels
+ *       running beside them.  host_dst must be device-accessible pinned memory (hipHostMalloc),
+ *       else REFT_EINVAL.
  * After the last bucket a completion event is recorded (see reft_snapshot_wait): the snapshot is
  * complete only when every bucket has landed (section 4.4: COMPLETED when all tensors are
  * snapshotted).  Postcondition: host_dst[0..L) == stream; host_dst[L..) untouched.
  *
  * span_ptrs[T]   host array of device pointers (may be NULL where the span has 0 bytes).
- * staging        staged path only: 256-byte-aligned device buffer of staging_bytes >=
+ * staging        NULL, or a 256-byte-aligned device buffer of staging_bytes >=
  *                reft_plan_staging_slot_bytes(plan); up to 64 slots are used.  Scratch contents;
  *                must not be shared with another call that may be in flight.
  * host_dst       host buffer of host_cap >= L bytes, pinned.
@@ -180,11 +184,11 @@ int reft_reconstruct_spans(reft_plan *plan, const void *const *shard_span_ptrs, 
                            reft_stream stream);
 
 /* ---- S5 + S7: load a shard from pinned host memory back into its tensors (section 4.3, step 1) ---
- * The inverse of reft_snapshot_pack, with the same two transports: direct (the scatter kernel
- * reads the pinned host snapshot across the link, per bucket, on unpack_stream) or staged
- * (hipMemcpyAsync host_src + B_b -> staging slot on copy_stream, then a scatter kernel on
- * unpack_stream).  host_bytes must equal L (REFT_ESIZE).  Other arguments as for
- * reft_snapshot_pack.
+ * The inverse of reft_snapshot_pack, with the same two transports: staged (staging != NULL:
+ * hipMemcpyAsync host_src + B_b -> staging slot on copy_stream, then a scatter kernel on
+ * unpack_stream) or direct (staging == NULL: the scatter kernel reads the pinned host snapshot
+ * across the link, per bucket, on unpack_stream).  host_bytes must equal L (REFT_ESIZE).  Other
+ * arguments as for reft_snapshot_pack.
  */
 int reft_restore(reft_plan *plan, const void *host_src, uint64_t host_bytes,
                  void *staging, uint64_t staging_bytes,
@@ -197,8 +201,6 @@ int reft_restore_wait(reft_plan *plan);
  *                  a snapshot kernel on few compute units while training kernels run beside it.
  *   "nontemporal"  1 = streaming (non-temporal) loads and stores in the kernels, 0 = plain.
  *   "unroll"       16-byte chunks in flight per thread and source: 1, 2 or 4.
- *   "host_path"    1 = snapshot/restore kernels access pinned host memory directly (default),
- *                  0 = staging ring + hipMemcpyAsync.
  *   "link_wgs"     cap on workgroups of kernels bound by the host link (default 32).
  * Read when a plan is created:
  *   "tile_shift"   log2 of the tile size in bytes, 12..24 (default 18 = 256 KiB).

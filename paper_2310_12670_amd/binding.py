@@ -212,7 +212,7 @@ def reft_snapshot_pack(plan, span_ptrs, staging, host_dst, pack_stream=None, cop
                        staging_bytes: Optional[int] = None, host_cap: Optional[int] = None) -> None:
     _check(_load().reft_snapshot_pack(
         plan, ptr_array(span_ptrs), _addr(staging),
-        _nbytes(staging) if staging_bytes is None else int(staging_bytes),
+        (0 if staging is None else _nbytes(staging)) if staging_bytes is None else int(staging_bytes),
         _addr(host_dst), _nbytes(host_dst) if host_cap is None else int(host_cap),
         _stream(pack_stream), _stream(copy_stream)))
 
@@ -263,7 +263,8 @@ def reft_restore(plan, host_src, staging, span_ptrs, copy_stream=None, unpack_st
                  host_bytes: Optional[int] = None, staging_bytes: Optional[int] = None) -> None:
     _check(_load().reft_restore(
         plan, _addr(host_src), _nbytes(host_src) if host_bytes is None else int(host_bytes),
-        _addr(staging), _nbytes(staging) if staging_bytes is None else int(staging_bytes),
+        _addr(staging),
+        (0 if staging is None else _nbytes(staging)) if staging_bytes is None else int(staging_bytes),
         ptr_array(span_ptrs), _stream(copy_stream), _stream(unpack_stream)))
 
 

@@ -40,7 +40,6 @@ static std::atomic<uint64_t> g_nontemporal{1};
 static std::atomic<uint64_t> g_unroll{4};
 static std::atomic<uint64_t> g_tile_shift{18};   // read at plan creation
 static std::atomic<uint64_t> g_host_only{0};     // read at plan creation: no device tables
-static std::atomic<uint64_t> g_host_path{1};     // 1 = kernels access pinned host memory directly
 static std::atomic<uint64_t> g_link_wgs{32};     // grid cap of kernels bound by the host link
 
 extern "C" int reft_set_tunable(const char *name, uint64_t value)
@@ -59,9 +58,6 @@ extern "C" int reft_set_tunable(const char *name, uint64_t value)
     } else if (!strcmp(name, "tile_shift")) {
         if (value < 12 || value > 24) return fail(REFT_EINVAL, "tile_shift must be in [12, 24]");
         g_tile_shift = value;
-    } else if (!strcmp(name, "host_path")) {
-        if (value > 1) return fail(REFT_EINVAL, "host_path must be 0 (staged DMA) or 1 (direct)");
-        g_host_path = value;
     } else if (!strcmp(name, "link_wgs")) {
         if (value < 1 || value > (1u << 20)) return fail(REFT_EINVAL, "link_wgs out of range");
         g_link_wgs = value;
@@ -82,7 +78,6 @@ extern "C" int reft_get_tunable(const char *name, uint64_t *value)
     else if (!strcmp(name, "unroll")) *value = g_unroll;
     else if (!strcmp(name, "tile_shift")) *value = g_tile_shift;
     else if (!strcmp(name, "host_only_plans")) *value = g_host_only;
-    else if (!strcmp(name, "host_path")) *value = g_host_path;
     else if (!strcmp(name, "link_wgs")) *value = g_link_wgs;
     else return fail(REFT_EINVAL, "unknown tunable '%s'", name);
     return REFT_OK;
@@ -469,13 +464,13 @@ extern "C" int reft_snapshot_pack(reft_plan *p, const void *const *span_ptrs, vo
     const uint64_t *tab = nullptr;
     int entry = 0;
 
-    if (g_host_path.load() == 1) {
+    if (!staging) {
         // Direct path: the gather kernel stores straight into the pinned host buffer over the
         // host link, one launch per bucket, in order on pack_stream.  No staging, no DMA.
         const uint64_t hview = p->L ? device_view_of_host(host_dst) : 0;
         if (p->L && !hview)
             return fail(REFT_EINVAL, "reft_snapshot_pack: host buffer is not mapped for device "
-                                     "access (not pinned); set tunable host_path=0 to stage it");
+                                     "access (not pinned); pass a staging ring to copy it by DMA");
         if ((rc = upload_ptrs(p, span_ptrs, 1, ps, &tab, &entry))) return rc;
         const LaunchCfg cfg = link_cfg(p);
         for (uint64_t b = 0; b < p->NB; ++b)
@@ -731,12 +726,12 @@ extern "C" int reft_restore(reft_plan *p, const void *host_src, uint64_t host_by
     const uint64_t *tab = nullptr;
     int entry = 0;
 
-    if (g_host_path.load() == 1) {
+    if (!staging) {
         // Direct path: the scatter kernel loads the snapshot from pinned host memory itself.
         const uint64_t hview = p->L ? device_view_of_host(host_src) : 0;
         if (p->L && !hview)
             return fail(REFT_EINVAL, "reft_restore: host buffer is not mapped for device access "
-                                     "(not pinned); set tunable host_path=0 to stage it");
+                                     "(not pinned); pass a staging ring to copy it by DMA");
         if ((rc = upload_ptrs(p, span_ptrs, 1, us, &tab, &entry))) return rc;
         const LaunchCfg cfg = link_cfg(p);
         for (uint64_t b = 0; b < p->NB; ++b)

@@ -18,6 +18,7 @@ pytestmark = pytest.mark.gpu
 
 GUARD = 512
 CANARY = 0xC3
+DIRECT = False      # set per test: snapshot / restore without a staging ring (kernels touch host)
 
 
 @pytest.fixture(scope="module")
@@ -31,9 +32,10 @@ def dev():
 @pytest.fixture(autouse=True, params=["direct", "staged"])
 def default_tunables(request):
     """Every case runs with both host transports; launch parameters are restored afterwards."""
-    names = ("max_wgs", "nontemporal", "unroll", "tile_shift", "host_path", "link_wgs")
+    global DIRECT
+    names = ("max_wgs", "nontemporal", "unroll", "tile_shift", "link_wgs")
     saved = {n: reft.reft_get_tunable(n) for n in names}
-    reft.reft_set_tunable("host_path", 1 if request.param == "direct" else 0)
+    DIRECT = request.param == "direct"
     yield
     for n, v in saved.items():
         reft.reft_set_tunable(n, v)
@@ -96,7 +98,8 @@ def run_case(dev, shards, sizes, buckets=None, uniform=0, lost=None, nslots=2, o
         streams = [oracle.pack_bucketed(c, blens) if L else np.zeros(0, np.uint8) for c in cpu]
 
         slot = reft.reft_plan_staging_slot_bytes(plan)
-        staging = torch.empty(max(256, nslots * slot), dtype=torch.uint8, device=dev)
+        staging = None if DIRECT else torch.empty(max(256, nslots * slot), dtype=torch.uint8,
+                                                  device=dev)
         s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
         torch.cuda.synchronize()
 
@@ -388,12 +391,10 @@ def test_size_and_argument_errors(dev):
             reft.reft_snapshot_pack(plan, spans, staging, host, host_cap=1023)
         assert e.value.code == reft.REFT_ESIZE
         with pytest.raises(reft.ReftError) as e:      # staging smaller than one slot
-            reft.reft_set_tunable("host_path", 0)
             reft.reft_snapshot_pack(plan, spans, staging, host, staging_bytes=512)
         assert e.value.code == reft.REFT_ESIZE
         with pytest.raises(reft.ReftError) as e:      # direct path needs pinned host memory
-            reft.reft_set_tunable("host_path", 1)
-            reft.reft_snapshot_pack(plan, spans, staging, np.zeros(2048, np.uint8))
+            reft.reft_snapshot_pack(plan, spans, None, np.zeros(2048, np.uint8))
         assert e.value.code == reft.REFT_EINVAL
         with pytest.raises(reft.ReftError) as e:      # restore of a snapshot of another length
             reft.reft_restore(plan, host, staging, spans, host_bytes=1025)
@@ -428,7 +429,7 @@ def test_back_to_back_snapshots_reuse_the_staging_ring(dev):
     plan = reft.reft_plan_create(sizes, None, 100003)
     try:
         slot = reft.reft_plan_staging_slot_bytes(plan)
-        staging = torch.empty(2 * slot, dtype=torch.uint8, device=dev)
+        staging = None if DIRECT else torch.empty(2 * slot, dtype=torch.uint8, device=dev)
         hosts = [Guarded(L, pinned=True) for _ in range(6)]
         s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
         torch.cuda.synchronize()
