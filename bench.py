@@ -57,6 +57,10 @@ def main() -> int:
     ap.add_argument("--staging-slots", type=int, default=16, help="slots per staging ring")
     ap.add_argument("--link-wgs", type=int, default=0,
                     help="cap on workgroups of the link-bound kernels (0 = library default)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain device-to-device copy of 1 GiB (torch), the kernel of "
+                         "known size that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--no-stages", action="store_true", help="skip the per-stage measurements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-mib", type=int, default=512,
                     help="bytes per shard of the CPU-oracle sample, MiB")
@@ -167,6 +171,13 @@ def main() -> int:
     def step(timed=False):
         load_phase(timed, save_phase(timed))
 
+    if args.calibration_copy:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(7)
+        b = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -190,55 +201,61 @@ def main() -> int:
     rec_gbps = (k + 1) * L / (rec_ms * 1e-3) / 1e9
 
     # ---- each stage alone --------------------------------------------------------------------
-    def timed_alone(fn, stream, reps=5):
-        fn()
-        torch.cuda.synchronize()
-        ts = []
-        for _ in range(reps):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            e0.record(stream)
-            fn()
-            e1.record(stream)
-            e1.synchronize()
-            ts.append(e0.elapsed_time(e1) * 1e-3)
-        ts.sort()
-        return ts[len(ts) // 2]
-
-    packed = torch.empty(L, dtype=torch.uint8, device=dev)
-    t_pack = timed_alone(lambda: reft.reft_pack_device(plan, p_own, packed, s_xor), s_xor)
-    t_unpack = timed_alone(lambda: reft.reft_unpack_device(plan, packed, p_fresh_own, s_xor), s_xor)
-    t_enc = timed_alone(lambda: reft.reft_parity_encode(plan, p_all, k, parity, s_xor), s_xor)
-    t_rec = timed_alone(lambda: reft.reft_reconstruct_spans(plan, p_surv, k, lost, parity2,
-                                                            p_fresh_lost, s_xor), s_xor)
-    del packed
-
-    def snap():
-        s_snap.wait_stream(s_xor)
-        reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_snap, s_copy)
-        s_xor.wait_stream(snap_done_stream)
-    def rest():
-        s_h2d.wait_stream(s_xor)
-        reft.reft_restore(plan, host_snap, stag_load, p_fresh_own, s_h2d, s_load)
-        s_xor.wait_stream(s_load)
-    t_snap = timed_alone(snap, s_xor, reps=3)
-    t_rest = timed_alone(rest, s_xor, reps=3)
-
     def pct(x, peak):
         return round(100.0 * x / peak, 1)
-    stages = {
-        "pack_kernel_GBps": round(2 * L / t_pack / 1e9, 1),
-        "unpack_kernel_GBps": round(2 * L / t_unpack / 1e9, 1),
-        "parity_encode_GBps": round((k + 1) * L / t_enc / 1e9, 1),
-        "reconstruct_GBps": round((k + 1) * L / t_rec / 1e9, 1),
-        "snapshot_d2h_GBps": round(L / t_snap / 1e9, 2),
-        "restore_h2d_GBps": round(L / t_rest / 1e9, 2),
-    }
-    stages["pct_hbm_peak"] = {n: pct(stages[n], HBM_PEAK_GBPS) for n in
-                              ("pack_kernel_GBps", "unpack_kernel_GBps", "parity_encode_GBps",
-                               "reconstruct_GBps")}
-    stages["pct_link_peak"] = {n: pct(stages[n], LINK_PEAK_GBPS) for n in
-                               ("snapshot_d2h_GBps", "restore_h2d_GBps")}
+
+    def measure_stages():
+        def timed_alone(fn, stream, reps=5):
+            fn()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(reps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record(stream)
+                fn()
+                e1.record(stream)
+                e1.synchronize()
+                ts.append(e0.elapsed_time(e1) * 1e-3)
+            ts.sort()
+            return ts[len(ts) // 2]
+
+        packed = torch.empty(L, dtype=torch.uint8, device=dev)
+        t_pack = timed_alone(lambda: reft.reft_pack_device(plan, p_own, packed, s_xor), s_xor)
+        t_unpack = timed_alone(lambda: reft.reft_unpack_device(plan, packed, p_fresh_own, s_xor), s_xor)
+        t_enc = timed_alone(lambda: reft.reft_parity_encode(plan, p_all, k, parity, s_xor), s_xor)
+        t_rec = timed_alone(lambda: reft.reft_reconstruct_spans(plan, p_surv, k, lost, parity2,
+                                                                p_fresh_lost, s_xor), s_xor)
+        del packed
+
+        def snap():
+            s_snap.wait_stream(s_xor)
+            reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_snap, s_copy)
+            s_xor.wait_stream(snap_done_stream)
+        def rest():
+            s_h2d.wait_stream(s_xor)
+            reft.reft_restore(plan, host_snap, stag_load, p_fresh_own, s_h2d, s_load)
+            s_xor.wait_stream(s_load)
+        t_snap = timed_alone(snap, s_xor, reps=3)
+        t_rest = timed_alone(rest, s_xor, reps=3)
+
+        stages = {
+            "pack_kernel_GBps": round(2 * L / t_pack / 1e9, 1),
+            "unpack_kernel_GBps": round(2 * L / t_unpack / 1e9, 1),
+            "parity_encode_GBps": round((k + 1) * L / t_enc / 1e9, 1),
+            "reconstruct_GBps": round((k + 1) * L / t_rec / 1e9, 1),
+            "snapshot_d2h_GBps": round(L / t_snap / 1e9, 2),
+            "restore_h2d_GBps": round(L / t_rest / 1e9, 2),
+        }
+        stages["pct_hbm_peak"] = {n: pct(stages[n], HBM_PEAK_GBPS) for n in
+                                  ("pack_kernel_GBps", "unpack_kernel_GBps", "parity_encode_GBps",
+                                   "reconstruct_GBps")}
+        stages["pct_link_peak"] = {n: pct(stages[n], LINK_PEAK_GBPS) for n in
+                                   ("snapshot_d2h_GBps", "restore_h2d_GBps")}
+
+        return stages
+
+    stages = None if args.no_stages else measure_stages()
 
     # ---- concurrent training proxy: bf16 8192^3 GEMMs beside the save phase -------------------
     gemm = None
@@ -339,7 +356,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(enc_gbps / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            "traffic": measured_traffic(wl.cfg) if k == 8 else None,
             "bytes_per_launch": (k + 1) * L,
             "avg_launch_ms": round(enc_ms, 3),
             "reconstruct_achieved": round(rec_gbps, 1),
@@ -353,6 +370,24 @@ def main() -> int:
     reft.reft_plan_destroy(pplan)
     print(json.dumps(record), flush=True)
     return 0 if verified else 1
+
+
+def measured_traffic(cfg: int):
+    """HBM bytes per launch of the encode kernel from the committed rocprofv3 counter runs
+    (FETCH_SIZE and WRITE_SIZE, each scaled by a copy of known size), or None if no such profile
+    exists for this configuration."""
+    path = os.path.join(ROOT, "profiles", f"config{cfg}_k_gather8_hbm_traffic.txt")
+    try:
+        kv = {}
+        for line in open(path):
+            if "=" in line and line.split("=")[0].strip().startswith("traffic_"):
+                key, _, val = line.partition("=")
+                kv[key.strip()] = val.strip()
+        if int(kv.get("traffic_config", -1)) == cfg:
+            return int(kv["traffic_bytes"])
+    except (OSError, ValueError, KeyError):
+        pass
+    return None
 
 
 def cpu_baseline(wl, shards, own, lost, sample_bytes):
