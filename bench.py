@@ -54,7 +54,8 @@ def main() -> int:
                          "to pinned host memory itself")
     ap.add_argument("--load-path", choices=["direct", "staged"], default="direct",
                     help="restore transport (recovery: the GPU is otherwise idle)")
-    ap.add_argument("--staging-slots", type=int, default=16, help="slots per staging ring")
+    ap.add_argument("--staging-mib", type=int, default=1024,
+                    help="size of each staging ring in MiB (split into bucket-sized slots)")
     ap.add_argument("--link-wgs", type=int, default=0,
                     help="cap on workgroups of the link-bound kernels (0 = library default)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -100,8 +101,9 @@ def main() -> int:
     def ring(p, use):
         if not use:
             return None
-        return torch.empty(args.staging_slots * reft.reft_plan_staging_slot_bytes(p),
-                           dtype=torch.uint8, device=dev)
+        slot = reft.reft_plan_staging_slot_bytes(p)
+        nslots = max(2, min(64, (args.staging_mib << 20) // slot))
+        return torch.empty(nslots * slot, dtype=torch.uint8, device=dev)
     stag_save, stag_psave = ring(plan, save_staged), ring(pplan, save_staged)
     stag_load, stag_pload = ring(plan, load_staged), ring(pplan, load_staged)
     t0 = time.time()
@@ -343,7 +345,7 @@ def main() -> int:
                     "restore shard + parity from host and reconstruct the lost shard",
             "value_bytes_per_step": 4 * L,
             "save_path": args.save_path, "load_path": args.load_path,
-            "staging_slots": args.staging_slots,
+            "staging_mib": args.staging_mib,
             "link_wgs": reft.reft_get_tunable("link_wgs"),
             "pct_link_peak": pct(value, LINK_PEAK_GBPS),
         },

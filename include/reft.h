@@ -124,10 +124,46 @@ int reft_snapshot_pack(reft_plan *plan, const void *const *span_ptrs,
                        void *staging, uint64_t staging_bytes,
                        void *host_dst, uint64_t host_cap,
                        reft_stream pack_stream, reft_stream copy_stream);
+/* The same for the buckets [bucket_begin, bucket_end) only: the unit a scheduler places into a
+ * pipeline bubble or beside computation (Algorithm 1 launches W_bubble, the part of the flat vector
+ * before the SplitParameter cut, in bubble time and the rest in computation time).  The snapshot
+ * is complete when calls covering all buckets have landed.  REFT_EINVAL if the range is not within
+ * [0, NB].  reft_plan_bucket_of gives the bucket that holds a stream offset (offset == L gives NB).
+ */
+int reft_snapshot_pack_range(reft_plan *plan, const void *const *span_ptrs,
+                             void *staging, uint64_t staging_bytes,
+                             void *host_dst, uint64_t host_cap,
+                             uint64_t bucket_begin, uint64_t bucket_end,
+                             reft_stream pack_stream, reft_stream copy_stream);
+int reft_plan_bucket_of(const reft_plan *plan, uint64_t offset, uint64_t *bucket);
 /* Block until the most recent reft_snapshot_pack on this plan has fully landed on the host. */
 int reft_snapshot_wait(reft_plan *plan);
 /* 1 if it has landed (or none was issued), 0 if still in flight, negative on error. */
 int reft_snapshot_query(reft_plan *plan);
+
+/* ---- completed / ongoing snapshot pair (section 4.4, Snapshot Management) --------------------------
+ * Host memory keeps one completed snapshot while the next one is being written; the new one
+ * replaces the old only when all of it has landed, so an interrupted save never damages the copy a
+ * recovery would load.  A reft_ckpt tracks two caller-owned pinned buffers of `cap` >= L bytes:
+ *   reft_ckpt_begin   picks the buffer that does NOT hold the newest complete snapshot, marks it
+ *                     as being overwritten and returns it (*host_dst) with a new generation number;
+ *   (the caller then issues reft_snapshot_pack / _range calls into *host_dst)
+ *   reft_ckpt_commit  enqueues, on the stream on which the last bucket lands (copy_stream for the
+ *                     staged transport, pack_stream for the direct one), a one-thread kernel that
+ *                     stores the generation into a pinned flag after everything queued before it:
+ *                     the COMPLETED mark of section 4.4;
+ *   reft_ckpt_latest  returns the newest buffer whose flag equals the generation begun in it
+ *                     (*host_src == NULL, generation 0 if there is none yet).  Never blocks.
+ * Errors: REFT_EINVAL (null arguments, commit without begin), REFT_ESIZE (cap < L), REFT_EHIP.
+ * Not thread-safe; one snapshot in progress per reft_ckpt.
+ */
+typedef struct reft_ckpt reft_ckpt;
+int reft_ckpt_create(reft_plan *plan, void *host_buf0, void *host_buf1, uint64_t cap,
+                     reft_ckpt **out);
+void reft_ckpt_destroy(reft_ckpt *ckpt);
+int reft_ckpt_begin(reft_ckpt *ckpt, void **host_dst, uint64_t *generation);
+int reft_ckpt_commit(reft_ckpt *ckpt, reft_stream stream);
+int reft_ckpt_latest(reft_ckpt *ckpt, const void **host_src, uint64_t *generation);
 
 /* ---- S1 alone / S7 alone: the gather and scatter kernels between device buffers ------------------
  * reft_pack_device:   dst_dev[0..L) = stream of the spans           (one launch over [0, L)).

@@ -19,7 +19,9 @@ __all__ = [
     "reft_plan_num_buckets", "reft_plan_max_bucket_bytes", "reft_plan_staging_slot_bytes",
     "reft_plan_bucket_range", "reft_plan_split", "reft_plan_span_offset", "reft_plan_tile_info",
     "reft_plan_tile_first_span",
-    "reft_snapshot_pack", "reft_snapshot_wait", "reft_snapshot_query",
+    "reft_snapshot_pack", "reft_snapshot_pack_range", "reft_plan_bucket_of", "reft_snapshot_wait",
+    "reft_snapshot_query", "reft_ckpt_create", "reft_ckpt_destroy", "reft_ckpt_begin",
+    "reft_ckpt_commit", "reft_ckpt_latest",
     "reft_pack_device", "reft_unpack_device", "reft_parity_encode", "reft_reconstruct",
     "reft_reconstruct_spans", "reft_restore", "reft_restore_wait",
     "reft_set_tunable", "reft_get_tunable", "reft_last_error", "reft_version",
@@ -69,6 +71,13 @@ def _load():
         "reft_plan_tile_first_span": (i, [vp, u64, pu64]),
         "reft_plan_split": (i, [vp, ctypes.c_double, ctypes.c_double, pu64]),
         "reft_snapshot_pack": (i, [vp, vp, vp, u64, vp, u64, vp, vp]),
+        "reft_snapshot_pack_range": (i, [vp, vp, vp, u64, vp, u64, u64, u64, vp, vp]),
+        "reft_plan_bucket_of": (i, [vp, u64, pu64]),
+        "reft_ckpt_create": (i, [vp, vp, vp, u64, ctypes.POINTER(vp)]),
+        "reft_ckpt_destroy": (None, [vp]),
+        "reft_ckpt_begin": (i, [vp, ctypes.POINTER(vp), pu64]),
+        "reft_ckpt_commit": (i, [vp, vp]),
+        "reft_ckpt_latest": (i, [vp, ctypes.POINTER(vp), pu64]),
         "reft_snapshot_wait": (i, [vp]),
         "reft_snapshot_query": (i, [vp]),
         "reft_pack_device": (i, [vp, vp, vp, u64, vp]),
@@ -215,6 +224,53 @@ def reft_snapshot_pack(plan, span_ptrs, staging, host_dst, pack_stream=None, cop
         (0 if staging is None else _nbytes(staging)) if staging_bytes is None else int(staging_bytes),
         _addr(host_dst), _nbytes(host_dst) if host_cap is None else int(host_cap),
         _stream(pack_stream), _stream(copy_stream)))
+
+
+def reft_snapshot_pack_range(plan, span_ptrs, staging, host_dst, bucket_begin: int, bucket_end: int,
+                             pack_stream=None, copy_stream=None,
+                             staging_bytes: Optional[int] = None,
+                             host_cap: Optional[int] = None) -> None:
+    _check(_load().reft_snapshot_pack_range(
+        plan, ptr_array(span_ptrs), _addr(staging),
+        (0 if staging is None else _nbytes(staging)) if staging_bytes is None else int(staging_bytes),
+        _addr(host_dst), _nbytes(host_dst) if host_cap is None else int(host_cap),
+        int(bucket_begin), int(bucket_end), _stream(pack_stream), _stream(copy_stream)))
+
+
+def reft_plan_bucket_of(plan, offset: int) -> int:
+    b = ctypes.c_uint64()
+    _check(_load().reft_plan_bucket_of(plan, int(offset), ctypes.byref(b)))
+    return b.value
+
+
+def reft_ckpt_create(plan, host_buf0, host_buf1, cap: Optional[int] = None) -> int:
+    out = ctypes.c_void_p()
+    _check(_load().reft_ckpt_create(plan, _addr(host_buf0), _addr(host_buf1),
+                                    min(_nbytes(host_buf0), _nbytes(host_buf1)) if cap is None
+                                    else int(cap), ctypes.byref(out)))
+    return out.value
+
+
+def reft_ckpt_destroy(ckpt) -> None:
+    _load().reft_ckpt_destroy(ckpt)
+
+
+def reft_ckpt_begin(ckpt):
+    """(address of the ongoing host buffer, generation)"""
+    dst, gen = ctypes.c_void_p(), ctypes.c_uint64()
+    _check(_load().reft_ckpt_begin(ckpt, ctypes.byref(dst), ctypes.byref(gen)))
+    return dst.value, gen.value
+
+
+def reft_ckpt_commit(ckpt, stream=None) -> None:
+    _check(_load().reft_ckpt_commit(ckpt, _stream(stream)))
+
+
+def reft_ckpt_latest(ckpt):
+    """(address of the newest complete host snapshot or None, its generation or 0)"""
+    src, gen = ctypes.c_void_p(), ctypes.c_uint64()
+    _check(_load().reft_ckpt_latest(ckpt, ctypes.byref(src), ctypes.byref(gen)))
+    return src.value, gen.value
 
 
 def reft_snapshot_wait(plan) -> None:

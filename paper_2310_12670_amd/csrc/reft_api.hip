@@ -448,12 +448,17 @@ static int staging_slots(const reft_plan *p, const void *staging, uint64_t stagi
     return REFT_OK;
 }
 
-extern "C" int reft_snapshot_pack(reft_plan *p, const void *const *span_ptrs, void *staging,
-                                  uint64_t staging_bytes, void *host_dst, uint64_t host_cap,
-                                  reft_stream pack_stream, reft_stream copy_stream)
+extern "C" int reft_snapshot_pack_range(reft_plan *p, const void *const *span_ptrs, void *staging,
+                                        uint64_t staging_bytes, void *host_dst, uint64_t host_cap,
+                                        uint64_t bucket_begin, uint64_t bucket_end,
+                                        reft_stream pack_stream, reft_stream copy_stream)
 {
     int rc = check_plan(p, "reft_snapshot_pack");
     if (rc) return rc;
+    if (bucket_begin > bucket_end || bucket_end > p->NB)
+        return fail(REFT_EINVAL, "reft_snapshot_pack: bucket range [%llu, %llu) outside [0, %llu]",
+                    (unsigned long long)bucket_begin, (unsigned long long)bucket_end,
+                    (unsigned long long)p->NB);
     if ((rc = check_span_ptrs(p, span_ptrs, 1, "reft_snapshot_pack"))) return rc;
     if (host_cap < p->L)
         return fail(REFT_ESIZE, "reft_snapshot_pack: host buffer holds %llu bytes, stream has %llu",
@@ -473,7 +478,7 @@ extern "C" int reft_snapshot_pack(reft_plan *p, const void *const *span_ptrs, vo
                                      "access (not pinned); pass a staging ring to copy it by DMA");
         if ((rc = upload_ptrs(p, span_ptrs, 1, ps, &tab, &entry))) return rc;
         const LaunchCfg cfg = link_cfg(p);
-        for (uint64_t b = 0; b < p->NB; ++b)
+        for (uint64_t b = bucket_begin; b < bucket_end; ++b)
             HIPCHK(launch_gather(pt, tab, 1, false, nullptr, hview, p->bstart[b], p->bstart[b + 1],
                                  cfg, ps));
         if ((rc = record(p->ring_ev[entry], ps))) return rc;
@@ -491,9 +496,9 @@ extern "C" int reft_snapshot_pack(reft_plan *p, const void *const *span_ptrs, vo
     const int ngroups = nslots >= kGroups ? kGroups : 1;
     const uint64_t per_group = (uint64_t)(nslots / ngroups);
     uint64_t batch = 0;
-    for (uint64_t b0 = 0; b0 < p->NB; b0 += per_group, ++batch) {
+    for (uint64_t b0 = bucket_begin; b0 < bucket_end; b0 += per_group, ++batch) {
         const int g = (int)(batch % (uint64_t)ngroups);
-        const uint64_t b1 = b0 + per_group < p->NB ? b0 + per_group : p->NB;
+        const uint64_t b1 = b0 + per_group < bucket_end ? b0 + per_group : bucket_end;
         // the group's previous occupants must have left for the host
         if ((rc = wait_on(ps, p->pack_free[g]))) return rc;
         for (uint64_t b = b0; b < b1; ++b) {
@@ -519,6 +524,29 @@ extern "C" int reft_snapshot_pack(reft_plan *p, const void *const *span_ptrs, vo
     return record(p->pack_done, cs);
 }
 
+extern "C" int reft_snapshot_pack(reft_plan *p, const void *const *span_ptrs, void *staging,
+                                  uint64_t staging_bytes, void *host_dst, uint64_t host_cap,
+                                  reft_stream pack_stream, reft_stream copy_stream)
+{
+    return reft_snapshot_pack_range(p, span_ptrs, staging, staging_bytes, host_dst, host_cap, 0,
+                                    p ? p->NB : 0, pack_stream, copy_stream);
+}
+
+extern "C" int reft_plan_bucket_of(const reft_plan *p, uint64_t offset, uint64_t *bucket)
+{
+    if (!p || !bucket) return fail(REFT_EINVAL, "reft_plan_bucket_of: null argument");
+    if (offset > p->L) return fail(REFT_EINVAL, "reft_plan_bucket_of: offset beyond the stream");
+    // number of buckets that end at or before `offset` = index of the bucket holding it
+    uint64_t lo = 0, hi = p->NB;
+    while (lo < hi) {
+        const uint64_t mid = (lo + hi) / 2;
+        if (p->bstart[mid + 1] <= offset) lo = mid + 1;
+        else hi = mid;
+    }
+    *bucket = lo;
+    return REFT_OK;
+}
+
 extern "C" int reft_snapshot_wait(reft_plan *p)
 {
     int rc = check_plan(p, "reft_snapshot_wait");
@@ -536,6 +564,118 @@ extern "C" int reft_snapshot_query(reft_plan *p)
     if (e == hipSuccess) return 1;
     if (e == hipErrorNotReady) return 0;
     return fail(REFT_EHIP, "hipEventQuery failed: %s", hipGetErrorString(e));
+}
+
+// ------------------------------------------------------------------------------------------------
+// completed / ongoing snapshot pair
+// ------------------------------------------------------------------------------------------------
+struct reft_ckpt {
+    reft_plan *plan = nullptr;
+    void *buf[2] = {nullptr, nullptr};
+    uint64_t cap = 0;
+    // pinned, device-visible: committed[i] = generation whose every byte has landed in buf[i]
+    uint64_t *committed = nullptr;
+    uint64_t begun[2] = {0, 0};      // generation most recently started in buf[i] (host side)
+    uint64_t generation = 0;
+    int ongoing = -1;                // buffer of the snapshot in progress, -1 if none
+};
+
+__global__ void k_commit(uint64_t *slot, uint64_t generation)
+{
+    // runs after every transfer queued before it on its stream; the store is visible to the host
+    __hip_atomic_store(slot, generation, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+extern "C" int reft_ckpt_create(reft_plan *p, void *host_buf0, void *host_buf1, uint64_t cap,
+                                reft_ckpt **out)
+{
+    if (!out) return fail(REFT_EINVAL, "reft_ckpt_create: null out");
+    *out = nullptr;
+    int rc = check_plan(p, "reft_ckpt_create");
+    if (rc) return rc;
+    if (!host_buf0 || !host_buf1 || host_buf0 == host_buf1)
+        return fail(REFT_EINVAL, "reft_ckpt_create: need two distinct host buffers");
+    if (cap < p->L) return fail(REFT_ESIZE, "reft_ckpt_create: buffers hold %llu bytes, stream has %llu",
+                                (unsigned long long)cap, (unsigned long long)p->L);
+    reft_ckpt *c = new (std::nothrow) reft_ckpt;
+    if (!c) return fail(REFT_EINVAL, "reft_ckpt_create: out of host memory");
+    c->plan = p;
+    c->buf[0] = host_buf0;
+    c->buf[1] = host_buf1;
+    c->cap = cap;
+    hipError_t e = hipHostMalloc((void **)&c->committed, 2 * sizeof(uint64_t), hipHostMallocDefault);
+    if (e != hipSuccess) {
+        delete c;
+        return fail(REFT_EHIP, "hipHostMalloc failed: %s", hipGetErrorString(e));
+    }
+    c->committed[0] = c->committed[1] = 0;
+    *out = c;
+    return REFT_OK;
+}
+
+extern "C" void reft_ckpt_destroy(reft_ckpt *c)
+{
+    if (!c) return;
+    if (c->committed) (void)hipHostFree(c->committed);
+    delete c;
+}
+
+static uint64_t committed_of(const reft_ckpt *c, int i)
+{
+    return __atomic_load_n(&c->committed[i], __ATOMIC_ACQUIRE);
+}
+
+// Index of the newest buffer whose snapshot is complete and not being overwritten, or -1.
+static int latest_complete(const reft_ckpt *c, uint64_t *gen)
+{
+    int best = -1;
+    uint64_t best_gen = 0;
+    for (int i = 0; i < 2; ++i) {
+        const uint64_t g = committed_of(c, i);
+        if (g != 0 && g == c->begun[i] && g > best_gen) {
+            best = i;
+            best_gen = g;
+        }
+    }
+    if (gen) *gen = best_gen;
+    return best;
+}
+
+extern "C" int reft_ckpt_begin(reft_ckpt *c, void **host_dst, uint64_t *generation)
+{
+    if (!c || !host_dst) return fail(REFT_EINVAL, "reft_ckpt_begin: null argument");
+    // write into the buffer that does not hold the newest complete snapshot
+    const int keep = latest_complete(c, nullptr);
+    const int i = keep == 0 ? 1 : 0;
+    c->generation += 1;
+    c->begun[i] = c->generation;     // from here until its commit lands, buffer i counts as torn
+    c->ongoing = i;
+    *host_dst = c->buf[i];
+    if (generation) *generation = c->generation;
+    return REFT_OK;
+}
+
+extern "C" int reft_ckpt_commit(reft_ckpt *c, reft_stream stream)
+{
+    if (!c) return fail(REFT_EINVAL, "reft_ckpt_commit: null argument");
+    if (c->ongoing < 0) return fail(REFT_EINVAL, "reft_ckpt_commit: no snapshot was begun");
+    int rc = check_plan(c->plan, "reft_ckpt_commit");
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_commit, dim3(1), dim3(1), 0, (hipStream_t)stream,
+                       c->committed + c->ongoing, c->begun[c->ongoing]);
+    HIPCHK(hipGetLastError());
+    c->ongoing = -1;
+    return REFT_OK;
+}
+
+extern "C" int reft_ckpt_latest(reft_ckpt *c, const void **host_src, uint64_t *generation)
+{
+    if (!c || !host_src) return fail(REFT_EINVAL, "reft_ckpt_latest: null argument");
+    uint64_t g = 0;
+    const int i = latest_complete(c, &g);
+    *host_src = i < 0 ? nullptr : c->buf[i];
+    if (generation) *generation = g;
+    return REFT_OK;
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -73,6 +73,11 @@ def test_plan_arithmetic_matches_numpy(host_only):
                 want = int(np.searchsorted(ends, t * tile, side="right"))
                 assert reft.reft_plan_tile_first_span(plan, t) == want
             assert reft.reft_plan_staging_slot_bytes(plan) >= (max(buckets) if buckets else 0) + 256
+            for o in [0, L] + [int(x) for x in rng.integers(0, L + 1, size=8)]:
+                want_b = int(np.searchsorted(bends, o, side="right")) if len(buckets) else 0
+                assert reft.reft_plan_bucket_of(plan, o) == want_b
+            with pytest.raises(reft.ReftError):
+                reft.reft_plan_bucket_of(plan, L + 1)
         finally:
             reft.reft_plan_destroy(plan)
 
