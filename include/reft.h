@@ -238,6 +238,9 @@ int reft_restore_wait(reft_plan *plan);
  *   "nontemporal"  1 = streaming (non-temporal) loads and stores in the kernels, 0 = plain.
  *   "unroll"       16-byte chunks in flight per thread and source: 1, 2 or 4.
  *   "link_wgs"     cap on workgroups of kernels bound by the host link (default 32).
+ *   "small_pieces" a tile in which at least this many spans start is processed by the LDS-staged
+ *                  small-piece path of the gather / scatter kernels (default 8; 4294967295 = never,
+ *                  0 = always).
  * Read when a plan is created:
  *   "tile_shift"   log2 of the tile size in bytes, 12..24 (default 18 = 256 KiB).
  *   "host_only_plans"  1 = reft_plan_create builds only the host-side sizing (no GPU needed);

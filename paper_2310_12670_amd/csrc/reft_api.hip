@@ -41,6 +41,7 @@ static std::atomic<uint64_t> g_unroll{4};
 static std::atomic<uint64_t> g_tile_shift{18};   // read at plan creation
 static std::atomic<uint64_t> g_host_only{0};     // read at plan creation: no device tables
 static std::atomic<uint64_t> g_link_wgs{32};     // grid cap of kernels bound by the host link
+static std::atomic<uint64_t> g_small_pieces{8}; // spans starting in a tile that switch it to LDS mode
 
 extern "C" int reft_set_tunable(const char *name, uint64_t value)
 {
@@ -61,6 +62,9 @@ extern "C" int reft_set_tunable(const char *name, uint64_t value)
     } else if (!strcmp(name, "link_wgs")) {
         if (value < 1 || value > (1u << 20)) return fail(REFT_EINVAL, "link_wgs out of range");
         g_link_wgs = value;
+    } else if (!strcmp(name, "small_pieces")) {
+        if (value > 0xffffffffull) return fail(REFT_EINVAL, "small_pieces out of range");
+        g_small_pieces = value;
     } else if (!strcmp(name, "host_only_plans")) {
         if (value > 1) return fail(REFT_EINVAL, "host_only_plans must be 0 or 1");
         g_host_only = value;
@@ -79,6 +83,7 @@ extern "C" int reft_get_tunable(const char *name, uint64_t *value)
     else if (!strcmp(name, "tile_shift")) *value = g_tile_shift;
     else if (!strcmp(name, "host_only_plans")) *value = g_host_only;
     else if (!strcmp(name, "link_wgs")) *value = g_link_wgs;
+    else if (!strcmp(name, "small_pieces")) *value = g_small_pieces;
     else return fail(REFT_EINVAL, "unknown tunable '%s'", name);
     return REFT_OK;
 }
@@ -129,7 +134,8 @@ static LaunchCfg launch_cfg(const reft_plan *p)
 {
     uint64_t w = g_max_wgs;
     if (w == 0) w = 16ull * (uint64_t)(p ? p->num_cus : 256);
-    return LaunchCfg{(uint32_t)w, (uint32_t)g_unroll.load(), g_nontemporal.load() != 0};
+    return LaunchCfg{(uint32_t)w, (uint32_t)g_unroll.load(), g_nontemporal.load() != 0,
+                     (uint32_t)g_small_pieces.load()};
 }
 
 // Kernels whose rate is set by the host link need only a few workgroups to saturate it.

@@ -13,6 +13,8 @@ struct LaunchCfg {
     uint32_t max_wgs;              // cap on the grid size (>= 1)
     uint32_t unroll;               // 1, 2 or 4 chunks of 16 B in flight per thread and source
     bool nontemporal;
+    uint32_t small_pieces;         // a tile in which at least this many spans start takes the
+                                   // LDS-staged small-piece path (0xffffffff = never)
 };
 
 // Device-side tables of a plan.

@@ -148,6 +148,189 @@ __device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], ui
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Tiles that hold many small pieces (many small tensors end to end).
+//
+// Walking such a tile piece by piece leaves most of the workgroup idle and pays a chain of scalar
+// table look-ups per piece.  Instead the slice of the plan that the tile needs - span offsets and
+// the span pointers of every source - is staged in LDS once, and the tile is cut into 16-byte
+// destination chunks that are dealt to the threads: each thread finds the span that owns its
+// chunk by binary search in the LDS copy of the offsets.  A chunk inside one span is moved as a
+// vector (realigned in registers if the source is not co-aligned); a chunk that straddles a span
+// boundary is assembled byte by byte.  At most kLdsSpans spans are staged per pass; a tile with
+// more is handled in several passes.
+// ------------------------------------------------------------------------------------------------
+constexpr uint32_t kLdsSpans = 256;
+
+// Largest q in [0, n) with off[q] <= x; requires off[0] <= x < off[n].  Zero-length spans
+// (off[q] == off[q+1]) are never returned.
+__device__ __forceinline__ uint32_t find_span(const uint64_t *off, uint32_t n, uint64_t x)
+{
+    uint32_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (off[mid] <= x) lo = mid;
+        else hi = mid;
+    }
+    return lo;
+}
+
+// XOR over the K sources of the byte at stream offset x, whose span is q or a later one.
+template <int K>
+__device__ __forceinline__ uint8_t xor_byte_at(const uint64_t *off, const uint64_t (*ptr)[kLdsSpans],
+                                               uint32_t &q, uint64_t x)
+{
+    while (x >= off[q + 1]) ++q;               // x < off[n] bounds the walk
+    const uint64_t r = x - off[q];
+    uint8_t v = ld8(ptr[0][q] + r);
+#pragma unroll
+    for (int j = 1; j < K; ++j) v ^= ld8(ptr[j][q] + r);
+    return v;
+}
+
+// Stream range [o, e) -> dst_vbase + x, spans and pointers of all K sources staged through LDS.
+// `i` is a span with off[i] <= o.  If acc, the destination's bytes are the K-th source.
+template <int K, bool NT>
+__device__ __forceinline__ void gather_small(const PlanTables &pt, const uint64_t *__restrict__ tab,
+                                             uint64_t dst_vbase, uint64_t o, uint64_t e, uint32_t i,
+                                             uint32_t acc, uint64_t *s_off,
+                                             uint64_t (*s_ptr)[kLdsSpans])
+{
+    const uint32_t tid = threadIdx.x;
+    while (o < e) {
+        // o < e <= L = off[T] keeps i < T
+        const uint32_t n = (uint32_t)(pt.T - i < kLdsSpans ? pt.T - i : kLdsSpans);
+        __syncthreads();                                   // the previous pass is done with LDS
+        for (uint32_t q = tid; q <= n; q += kThreads) s_off[q] = pt.off[i + q];
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            if (acc && j == K - 1) {
+                // the destination as a source: "span pointer" = address of the span's first byte
+                for (uint32_t q = tid; q < n; q += kThreads) s_ptr[j][q] = dst_vbase + pt.off[i + q];
+            } else {
+                for (uint32_t q = tid; q < n; q += kThreads)
+                    s_ptr[j][q] = tab[(uint64_t)j * pt.T + i + q];
+            }
+        }
+        __syncthreads();
+        const uint64_t sub_e = s_off[n] < e ? s_off[n] : e;
+        if (sub_e > o) {
+            const uint64_t d0 = dst_vbase + o;
+            uint32_t len = (uint32_t)(sub_e - o);
+            uint32_t head = (uint32_t)(0 - d0) & 15u;
+            if (head > len) head = len;
+            const uint32_t nb = (len - head) >> 4;
+            const uint32_t tail = (len - head) & 15u;
+            if (tid < 32) {                                // edge bytes, one per thread
+                uint32_t b = 0xffffffffu;
+                if (tid < head) b = tid;
+                else if (tid >= 16 && tid - 16 < tail) b = head + (nb << 4) + (tid - 16);
+                if (b != 0xffffffffu) {
+                    uint32_t q = find_span(s_off, n, o + b);
+                    st8(d0 + b, xor_byte_at<K>(s_off, s_ptr, q, o + b));
+                }
+            }
+            const uint64_t x0 = o + head;
+            gptr16 dp = as_g16(d0 + head);
+            for (uint32_t c = tid; c < nb; c += kThreads) {
+                const uint64_t x = x0 + ((uint64_t)c << 4);
+                uint32_t q = find_span(s_off, n, x);
+                u32x4 v;
+                if (x + 16 <= s_off[q + 1]) {              // the chunk lies inside one span
+                    const uint64_t r = x - s_off[q];
+                    v = load_any<NT>(s_ptr[0][q] + r, 0);
+#pragma unroll
+                    for (int j = 1; j < K; ++j) v ^= load_any<NT>(s_ptr[j][q] + r, 0);
+                } else {                                   // it straddles a span boundary
+                    uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+                    for (int b = 0; b < 16; ++b)
+                        w[b >> 2] |= (uint32_t)xor_byte_at<K>(s_off, s_ptr, q, x + b) << ((b & 3) * 8);
+                    v.x = w[0]; v.y = w[1]; v.z = w[2]; v.w = w[3];
+                }
+                st16<NT>(dp + c, v);
+            }
+        }
+        o = sub_e > o ? sub_e : o;
+        i += n;
+    }
+}
+
+// Stream range [o, e) at src_vbase + x -> the spans' own places, span table staged through LDS.
+template <bool NT>
+__device__ __forceinline__ void scatter_small(const PlanTables &pt, const uint64_t *__restrict__ tab,
+                                              uint64_t src_vbase, uint64_t o, uint64_t e, uint32_t i,
+                                              uint64_t *s_off, uint64_t (*s_ptr)[kLdsSpans])
+{
+    const uint32_t tid = threadIdx.x;
+    while (o < e) {
+        const uint32_t n = (uint32_t)(pt.T - i < kLdsSpans ? pt.T - i : kLdsSpans);
+        __syncthreads();
+        for (uint32_t q = tid; q <= n; q += kThreads) s_off[q] = pt.off[i + q];
+        for (uint32_t q = tid; q < n; q += kThreads) s_ptr[0][q] = tab[i + q];
+        __syncthreads();
+        const uint64_t sub_e = s_off[n] < e ? s_off[n] : e;
+        // Are all destinations of this pass co-aligned with the source stream?  (True for tensors
+        // whose sizes and addresses are multiples of 16.)  If not, 16-byte source chunks would
+        // have to be stored in narrow pieces; the piece routine, which realigns on the load side,
+        // is the better tool then, fed from the LDS copy of the tables.
+        int mis = 0;
+        for (uint32_t q = tid; q < n; q += kThreads)
+            if (s_off[q + 1] > s_off[q] && ((s_ptr[0][q] - (src_vbase + s_off[q])) & 15u)) mis = 1;
+        mis = __syncthreads_or(mis);
+        if (sub_e > o && mis) {
+            uint64_t x = o;
+            uint32_t q = find_span(s_off, n, x);
+            while (x < sub_e) {
+                while (s_off[q + 1] <= x) ++q;                 // x < sub_e <= off[n]
+                uint64_t pe = s_off[q + 1] < sub_e ? s_off[q + 1] : sub_e;
+                const uint64_t src1[1] = {src_vbase + x};
+                xor_piece<1, 1, NT>(s_ptr[0][q] + (x - s_off[q]), src1, (uint32_t)(pe - x));
+                x = pe;
+            }
+        } else if (sub_e > o) {
+            // chunks are aligned on the (contiguous) source side; each goes to its span's place
+            const uint64_t s0 = src_vbase + o;
+            uint32_t len = (uint32_t)(sub_e - o);
+            uint32_t head = (uint32_t)(0 - s0) & 15u;
+            if (head > len) head = len;
+            const uint32_t nb = (len - head) >> 4;
+            const uint32_t tail = (len - head) & 15u;
+            if (tid < 32) {
+                uint32_t b = 0xffffffffu;
+                if (tid < head) b = tid;
+                else if (tid >= 16 && tid - 16 < tail) b = head + (nb << 4) + (tid - 16);
+                if (b != 0xffffffffu) {
+                    const uint64_t x = o + b;
+                    const uint32_t q = find_span(s_off, n, x);
+                    st8(s_ptr[0][q] + (x - s_off[q]), ld8(s0 + b));
+                }
+            }
+            const uint64_t x0 = o + head;
+            gcptr16 sp = as_gc16(s0 + head);
+            for (uint32_t c = tid; c < nb; c += kThreads) {
+                const uint64_t x = x0 + ((uint64_t)c << 4);
+                uint32_t q = find_span(s_off, n, x);
+                const u32x4 v = ld16<NT>(sp + c);
+                const uint64_t d = s_ptr[0][q] + (x - s_off[q]);
+                if (x + 16 <= s_off[q + 1] && (d & 15u) == 0) {
+                    st16<NT>(as_g16(d), v);
+                } else {                                   // a span boundary inside the chunk
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int b = 0; b < 16; ++b) {
+                        const uint64_t xb = x + b;
+                        while (xb >= s_off[q + 1]) ++q;    // xb < sub_e <= off[n] bounds the walk
+                        st8(s_ptr[0][q] + (xb - s_off[q]), (uint8_t)(w[b >> 2] >> ((b & 3) * 8)));
+                    }
+                }
+            }
+        }
+        o = sub_e > o ? sub_e : o;
+        i += n;
+    }
+}
+
 // destination of stream byte o  <-  XOR over rows j < K of (tab[j*T + span(o)] + offset of o in
 // its span).  The destination is dst_vbase + o, or, if dtab is not null, ragged as well:
 // dtab[span(o)] + offset.  With acc != 0 only K-1 rows are read and the destination itself is the
@@ -155,16 +338,25 @@ __device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], ui
 template <int K, int U, bool NT>
 __global__ void __launch_bounds__(kThreads)
 k_gather(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *__restrict__ dtab,
-         uint64_t dst_vbase, uint64_t lo, uint64_t hi, uint32_t acc)
+         uint64_t dst_vbase, uint64_t lo, uint64_t hi, uint32_t acc, uint32_t small_pieces)
 {
+    __shared__ uint64_t s_off[kLdsSpans + 1];
+    __shared__ uint64_t s_ptr[K][kLdsSpans];
     const uint32_t sh = pt.tile_shift;
     const uint64_t t_last = (hi - 1) >> sh;
+    const uint64_t t_end = (pt.L - 1) >> sh;              // last tile of the stream
     for (uint64_t t = (lo >> sh) + blockIdx.x; t <= t_last; t += gridDim.x) {
         uint64_t o = t << sh;
         uint64_t e = o + (1ull << sh);
         if (o < lo) o = lo;
         if (e > hi) e = hi;
         uint32_t i = pt.first_span[t];
+        // spans that start inside this tile (an upper bound of its pieces minus one)
+        const uint32_t i_next = t < t_end ? pt.first_span[t + 1] : (uint32_t)(pt.T - 1);
+        if (dtab == nullptr && i_next - i >= small_pieces) {
+            gather_small<K, NT>(pt, tab, dst_vbase, o, e, i, acc, s_off, s_ptr);
+            continue;
+        }
         while (o < e) {
             // o < e <= L = off[T], so a span with off[i+1] > o exists at or after i
             while (pt.off[i + 1] <= o) ++i;
@@ -188,16 +380,24 @@ k_gather(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *__rest
 template <int U, bool NT>
 __global__ void __launch_bounds__(kThreads)
 k_scatter(PlanTables pt, const uint64_t *__restrict__ tab, uint64_t src_vbase, uint64_t lo,
-          uint64_t hi)
+          uint64_t hi, uint32_t small_pieces)
 {
+    __shared__ uint64_t s_off[kLdsSpans + 1];
+    __shared__ uint64_t s_ptr[1][kLdsSpans];
     const uint32_t sh = pt.tile_shift;
     const uint64_t t_last = (hi - 1) >> sh;
+    const uint64_t t_end = (pt.L - 1) >> sh;
     for (uint64_t t = (lo >> sh) + blockIdx.x; t <= t_last; t += gridDim.x) {
         uint64_t o = t << sh;
         uint64_t e = o + (1ull << sh);
         if (o < lo) o = lo;
         if (e > hi) e = hi;
         uint32_t i = pt.first_span[t];
+        const uint32_t i_next = t < t_end ? pt.first_span[t + 1] : (uint32_t)(pt.T - 1);
+        if (i_next - i >= small_pieces) {
+            scatter_small<NT>(pt, tab, src_vbase, o, e, i, s_off, s_ptr);
+            continue;
+        }
         while (o < e) {
             while (pt.off[i + 1] <= o) ++i;
             const uint64_t so = pt.off[i];
@@ -263,12 +463,12 @@ hipError_t launch_gather(const PlanTables &pt, const uint64_t *tab, int nrows, b
     if (lo >= hi) return hipSuccess;
     if (hi > pt.L) return hipErrorInvalidValue;
     void (*fn)(PlanTables, const uint64_t *, const uint64_t *, uint64_t, uint64_t, uint64_t,
-               uint32_t) = nullptr;
+               uint32_t, uint32_t) = nullptr;
     const int nsrc = nrows + (acc ? 1 : 0);
     REFT_PICK_K(k_gather, fn, nsrc)
     const uint64_t ntiles = ((hi - 1) >> pt.tile_shift) - (lo >> pt.tile_shift) + 1;
     hipLaunchKernelGGL(fn, dim3(grid_for(ntiles, cfg)), dim3(kThreads), 0, stream, pt, tab, dtab,
-                       dst_vbase, lo, hi, acc ? 1u : 0u);
+                       dst_vbase, lo, hi, acc ? 1u : 0u, cfg.small_pieces);
     return hipGetLastError();
 }
 
@@ -277,7 +477,7 @@ hipError_t launch_scatter(const PlanTables &pt, const uint64_t *tab, uint64_t sr
 {
     if (lo >= hi) return hipSuccess;
     if (hi > pt.L) return hipErrorInvalidValue;
-    void (*fn)(PlanTables, const uint64_t *, uint64_t, uint64_t, uint64_t) =
+    void (*fn)(PlanTables, const uint64_t *, uint64_t, uint64_t, uint64_t, uint32_t) =
         cfg.nontemporal
             ? (cfg.unroll == 1 ? k_scatter<1, true> : cfg.unroll == 2 ? k_scatter<2, true>
                                                                       : k_scatter<4, true>)
@@ -285,7 +485,7 @@ hipError_t launch_scatter(const PlanTables &pt, const uint64_t *tab, uint64_t sr
                                                                        : k_scatter<4, false>);
     const uint64_t ntiles = ((hi - 1) >> pt.tile_shift) - (lo >> pt.tile_shift) + 1;
     hipLaunchKernelGGL(fn, dim3(grid_for(ntiles, cfg)), dim3(kThreads), 0, stream, pt, tab,
-                       src_vbase, lo, hi);
+                       src_vbase, lo, hi, cfg.small_pieces);
     return hipGetLastError();
 }
 

@@ -29,13 +29,17 @@ def dev():
     return d
 
 
-@pytest.fixture(autouse=True, params=["direct", "staged"])
+@pytest.fixture(autouse=True, params=["direct", "staged", "direct-lds", "staged-lds"])
 def default_tunables(request):
-    """Every case runs with both host transports; launch parameters are restored afterwards."""
+    """Every case runs with both host transports, and with the kernels' LDS-staged small-piece
+    path forced on for every tile ("-lds"; by default only tiles with many small spans take it).
+    Launch parameters are restored afterwards."""
     global DIRECT
-    names = ("max_wgs", "nontemporal", "unroll", "tile_shift", "link_wgs")
+    names = ("max_wgs", "nontemporal", "unroll", "tile_shift", "link_wgs", "small_pieces")
     saved = {n: reft.reft_get_tunable(n) for n in names}
-    DIRECT = request.param == "direct"
+    DIRECT = request.param.startswith("direct")
+    if request.param.endswith("-lds"):
+        reft.reft_set_tunable("small_pieces", 0)
     yield
     for n, v in saved.items():
         reft.reft_set_tunable(n, v)
@@ -271,6 +275,33 @@ def test_edge_sizes_and_misalignment(dev, sizes, phase_mode):
     out_phase = 0 if phase_mode == "aligned" else int(rng.integers(1, 16))
     run_case(dev, shards, sizes, buckets, lost=None, nslots=2, out_phase=out_phase,
              fresh_phases=fresh_ph)
+
+
+@pytest.mark.parametrize("mean_size,tile_shift", [(100, 18), (700, 16), (3000, 18), (40, 14)])
+def test_thousands_of_tiny_spans(dev, mean_size, tile_shift):
+    """Many small tensors end to end: hundreds to thousands of spans per tile (several LDS passes
+    per tile), zero-length spans, odd sizes and odd addresses, next to a few large spans."""
+    reft.reft_set_tunable("tile_shift", tile_shift)
+    rng = np.random.default_rng(mean_size)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(mean_size)
+    T = 6000
+    sizes = [int(x) for x in rng.integers(0, 2 * mean_size, size=T)]
+    for i in rng.choice(T, size=T // 10, replace=False):
+        sizes[i] = 0
+    for i in rng.choice(T, size=5, replace=False):
+        sizes[i] = int(rng.integers(200000, 600000))
+    k = 3
+    shards, keep = [], []
+    for s in range(k):
+        ph = [int(x) for x in rng.integers(0, 16, size=T)] if s else [0] * T
+        arena, spans = arena_spans(sizes, ph, dev, gen)
+        keep.append(arena)
+        shards.append(spans)
+    L = sum(sizes)
+    run_case(dev, shards, sizes, random_buckets(L, rng, 30000, 400000), lost=1, nslots=2,
+             out_phase=int(rng.integers(0, 16)),
+             fresh_phases=[int(x) for x in rng.integers(0, 16, size=T)])
 
 
 def test_empty_stream(dev):
