@@ -54,6 +54,10 @@ def main() -> int:
                          "to pinned host memory itself")
     ap.add_argument("--load-path", choices=["direct", "staged"], default="direct",
                     help="restore transport (recovery: the GPU is otherwise idle)")
+    ap.add_argument("--one-stream-save", action="store_true",
+                    help="staged save: gather kernels and copies in order on one stream")
+    ap.add_argument("--one-stream-load", action="store_true",
+                    help="staged load: copies and scatter kernels in order on one stream")
     ap.add_argument("--staging-mib", type=int, default=1024,
                     help="size of each staging ring in MiB (split into bucket-sized slots)")
     ap.add_argument("--link-wgs", type=int, default=0,
@@ -63,7 +67,7 @@ def main() -> int:
                          "known size that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--no-stages", action="store_true", help="skip the per-stage measurements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-mib", type=int, default=512,
+    ap.add_argument("--cpu-sample-mib", type=int, default=2048,
                     help="bytes per shard of the CPU-oracle sample, MiB")
     args = ap.parse_args()
 
@@ -128,8 +132,8 @@ def main() -> int:
     # s_snap / s_load carry the link-bound work (and, staged, the gather / scatter kernels);
     # s_copy / s_h2d carry the DMA transfers of the staged path; s_xor the HBM-bound XOR kernels.
     s_snap, s_xor, s_load = (torch.cuda.Stream() for _ in range(3))
-    s_copy = torch.cuda.Stream() if save_staged else s_snap
-    s_h2d = torch.cuda.Stream() if load_staged else s_load
+    s_copy = torch.cuda.Stream() if save_staged and not args.one_stream_save else s_snap
+    s_h2d = torch.cuda.Stream() if load_staged and not args.one_stream_load else s_load
     snap_done_stream = s_copy
     enc_events, rec_events = [], []
 
