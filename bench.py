@@ -4,11 +4,14 @@
 One *step* is one pass of the whole path over one rank-shaped synthetic state, inputs resident in
 HBM before the clock starts:
 
-  save   reft_snapshot_pack   own shard   -> staging ring -> pinned host      (gather + D2H)
+  save   reft_snapshot_pack   own shard   -> pinned host   (staged transport: DMA copies straight
+                                                            from the tensors, gather kernel only
+                                                            for runs of small tensors)
          reft_parity_encode   k shards    -> parity (device)                  (k-way XOR, in place)
-         reft_snapshot_pack   parity      -> pinned host                      (gather + D2H)
-  load   reft_restore         host shard  -> staging ring -> fresh tensors    (H2D + scatter)
-         reft_restore         host parity -> device                           (H2D + scatter)
+         reft_snapshot_pack   parity      -> pinned host
+  load   reft_restore         host shard  -> fresh tensors  (direct transport: the scatter kernel
+                                                             reads pinned host memory itself)
+         reft_restore         host parity -> device
          reft_reconstruct_spans  k-1 survivors + parity -> lost shard's tensors (k-way XOR)
 
 ``value`` is the step's checkpoint traffic, 4*L bytes (shard + parity saved to host, shard + parity
@@ -54,6 +57,10 @@ def main() -> int:
                          "to pinned host memory itself")
     ap.add_argument("--load-path", choices=["direct", "staged"], default="direct",
                     help="restore transport (recovery: the GPU is otherwise idle)")
+    ap.add_argument("--no-overlap-load", action="store_true",
+                    help="start the load phase only when the whole save phase has landed (default: "
+                         "the own shard's restore starts as soon as its snapshot is on the host, "
+                         "beside the parity's snapshot, which uses the link's other direction)")
     ap.add_argument("--one-stream-save", action="store_true",
                     help="staged save: gather kernels and copies in order on one stream")
     ap.add_argument("--one-stream-load", action="store_true",
@@ -158,7 +165,10 @@ def main() -> int:
         """Restore of the own shard (as soon as its snapshot is complete: it shares the link with
         the parity's snapshot, in the other direction), then the parity, then the decode."""
         first = s_h2d
-        first.wait_event(own_done)
+        if not args.no_overlap_load:
+            first.wait_event(own_done)
+        else:
+            first.wait_stream(snap_done_stream)
         reft.reft_restore(plan, host_snap, stag_load, p_fresh_own, s_h2d, s_load)
         first.wait_stream(snap_done_stream)             # the parity is complete on the host
         reft.reft_restore(pplan, host_par, stag_pload, p_par2, s_h2d, s_load)
@@ -174,8 +184,17 @@ def main() -> int:
         s_snap.wait_stream(s_xor)
         s_snap.wait_stream(s_load)
 
+    in_flight = []
+
     def step(timed=False):
+        # Host-side pacing: at most two steps queued at once (a trainer takes one snapshot per
+        # iteration; thousands of queued copies and events only slow the runtime down).
+        if len(in_flight) >= 2:
+            in_flight.pop(0).synchronize()
         load_phase(timed, save_phase(timed))
+        done = torch.cuda.Event()
+        done.record(s_xor)                      # the decode is the last thing a step does
+        in_flight.append(done)
 
     if args.calibration_copy:
         a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(7)

@@ -96,12 +96,17 @@ int reft_plan_split(const reft_plan *plan, double t_bubble, double t_ss, uint64_
 /* ---- S1 + S2 + S3: bucketed snapshot of one shard into pinned host memory -----------------------
  * Bucket by bucket, in order, the shard's stream is moved from the ragged span tensors to
  * host_dst + B_b.  Two transports, chosen per call by the staging argument:
- *   staged (staging != NULL)  a gather kernel on pack_stream copies each bucket into a slot of the
- *       staging ring and a hipMemcpyAsync on copy_stream moves the slot to the host on the DMA
- *       engines, which leaves the compute units and their path to memory to training kernels
- *       running beside the snapshot.  The ring's slots form two groups used alternately, so
- *       gathers and copies overlap when staging holds >= 2 slots; the two streams synchronise
- *       through events once per group.  pack_stream may equal copy_stream (fully in order).
+ *   staged (staging != NULL)  the transport for snapshots taken beside training.  Every piece
+ *       (bucket x span) of at least "dma_min_bytes" is copied by hipMemcpyAsync on copy_stream
+ *       straight from its tensor to host_dst: no kernel runs, so kernels of the training step
+ *       are not disturbed.  Smaller pieces are copied the same way when few lie together; a run
+ *       of at least "gather_min_pieces" consecutive small pieces within a bucket is gathered by
+ *       one kernel launch on pack_stream into a slot of the staging ring and leaves as one copy
+ *       (many small tensors would otherwise mean thousands of tiny transfers).  The ring's slots
+ *       form two groups used alternately; the two streams synchronise through events once per
+ *       group.  pack_stream may equal copy_stream (fully in order).  The tensors are read in
+ *       pack_stream's order: work queued on pack_stream before the call (say, the kernel that
+ *       produced a parity buffer) completes before any byte is read, also by the copies.
  *   direct (staging == NULL)  the gather kernel itself stores into the pinned host buffer across
  *       the host link: one launch per bucket on pack_stream, capped at "link_wgs" workgroups (a
  *       few dozen saturate the link).  No staging memory, no DMA, no second pass over HBM;
@@ -221,8 +226,8 @@ int reft_reconstruct_spans(reft_plan *plan, const void *const *shard_span_ptrs, 
 
 /* ---- S5 + S7: load a shard from pinned host memory back into its tensors (section 4.3, step 1) ---
  * The inverse of reft_snapshot_pack, with the same two transports: staged (staging != NULL:
- * hipMemcpyAsync host_src + B_b -> staging slot on copy_stream, then a scatter kernel on
- * unpack_stream) or direct (staging == NULL: the scatter kernel reads the pinned host snapshot
+ * large pieces by hipMemcpyAsync on copy_stream straight into their tensors, runs of small pieces
+ * by hipMemcpyAsync into a staging slot and a scatter kernel on unpack_stream) or direct (staging == NULL: the scatter kernel reads the pinned host snapshot
  * across the link, per bucket, on unpack_stream).  host_bytes must equal L (REFT_ESIZE).  Other
  * arguments as for reft_snapshot_pack.
  */
@@ -238,6 +243,10 @@ int reft_restore_wait(reft_plan *plan);
  *   "nontemporal"  1 = streaming (non-temporal) loads and stores in the kernels, 0 = plain.
  *   "unroll"       16-byte chunks in flight per thread and source: 1, 2 or 4.
  *   "link_wgs"     cap on workgroups of kernels bound by the host link (default 32).
+ *   "dma_min_bytes"     staged transport: pieces of at least this size travel by DMA alone
+ *                  (default 65536; 0 = every piece; a huge value = none, everything is gathered).
+ *   "gather_min_pieces" staged transport: shortest run of smaller pieces that is gathered by a
+ *                  kernel instead of being copied piece by piece (default 8, at least 1).
  *   "small_pieces" a tile in which at least this many spans start is processed by the LDS-staged
  *                  small-piece path of the gather / scatter kernels (default 8; 4294967295 = never,
  *                  0 = always).

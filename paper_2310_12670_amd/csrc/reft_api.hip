@@ -42,6 +42,8 @@ static std::atomic<uint64_t> g_tile_shift{18};   // read at plan creation
 static std::atomic<uint64_t> g_host_only{0};     // read at plan creation: no device tables
 static std::atomic<uint64_t> g_link_wgs{32};     // grid cap of kernels bound by the host link
 static std::atomic<uint64_t> g_small_pieces{8}; // spans starting in a tile that switch it to LDS mode
+static std::atomic<uint64_t> g_dma_min{65536};   // pieces of at least this many bytes are copied by DMA
+static std::atomic<uint64_t> g_gather_min{8};    // shortest run of smaller pieces worth a gather kernel
 
 extern "C" int reft_set_tunable(const char *name, uint64_t value)
 {
@@ -62,6 +64,11 @@ extern "C" int reft_set_tunable(const char *name, uint64_t value)
     } else if (!strcmp(name, "link_wgs")) {
         if (value < 1 || value > (1u << 20)) return fail(REFT_EINVAL, "link_wgs out of range");
         g_link_wgs = value;
+    } else if (!strcmp(name, "dma_min_bytes")) {
+        g_dma_min = value;
+    } else if (!strcmp(name, "gather_min_pieces")) {
+        if (value < 1) return fail(REFT_EINVAL, "gather_min_pieces must be at least 1");
+        g_gather_min = value;
     } else if (!strcmp(name, "small_pieces")) {
         if (value > 0xffffffffull) return fail(REFT_EINVAL, "small_pieces out of range");
         g_small_pieces = value;
@@ -84,6 +91,8 @@ extern "C" int reft_get_tunable(const char *name, uint64_t *value)
     else if (!strcmp(name, "host_only_plans")) *value = g_host_only;
     else if (!strcmp(name, "link_wgs")) *value = g_link_wgs;
     else if (!strcmp(name, "small_pieces")) *value = g_small_pieces;
+    else if (!strcmp(name, "dma_min_bytes")) *value = g_dma_min;
+    else if (!strcmp(name, "gather_min_pieces")) *value = g_gather_min;
     else return fail(REFT_EINVAL, "unknown tunable '%s'", name);
     return REFT_OK;
 }
@@ -124,8 +133,8 @@ struct reft_plan {
     Event ring_ev[kRing];
     unsigned ring_next = 0;
     // bucket pipelines
-    Event pack_filled[kGroups], pack_free[kGroups], pack_done;
-    Event rest_filled[kGroups], rest_free[kGroups], rest_done;
+    Event pack_filled[kGroups], pack_free[kGroups], pack_done, pack_begin, rest_begin;
+    Event rest_filled[kGroups], rest_free[kGroups], rest_done, rest_copied;
 
     PlanTables tables() const { return PlanTables{d_off, d_first, T, L, tile_shift}; }
 };
@@ -337,7 +346,10 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
             (rc = make_event(p->rest_filled[i])) || (rc = make_event(p->rest_free[i])))
             return rc;
     }
-    if ((rc = make_event(p->pack_done)) || (rc = make_event(p->rest_done))) return rc;
+    if ((rc = make_event(p->pack_done)) || (rc = make_event(p->rest_done)) ||
+        (rc = make_event(p->rest_copied)) || (rc = make_event(p->pack_begin)) ||
+        (rc = make_event(p->rest_begin)))
+        return rc;
     if ((rc = ensure_ring(p, 8))) return rc;
 
     guard.p = nullptr;
@@ -365,6 +377,9 @@ extern "C" void reft_plan_destroy(reft_plan *p)
     }
     drain(p->pack_done);
     drain(p->rest_done);
+    drain(p->rest_copied);
+    drain(p->pack_begin);
+    drain(p->rest_begin);
     free_ring(p);
     if (p->d_off) (void)hipFree(p->d_off);
     if (p->d_first) (void)hipFree(p->d_first);
@@ -434,6 +449,65 @@ extern "C" int reft_plan_split(const reft_plan *p, double t_bubble, double t_ss,
 }
 
 // ------------------------------------------------------------------------------------------------
+// how the bytes of a bucket range travel between the tensors and the host (staged transport)
+// ------------------------------------------------------------------------------------------------
+namespace {
+struct Run {            // stream range [a, b) of consecutive small pieces: gather kernel + one copy
+    uint64_t a, b;
+};
+struct Dma {            // one piece (bucket x span) copied by the DMA path straight from its tensor
+    uint64_t o, n, span;
+};
+}  // namespace
+
+// A piece of at least dma_min bytes needs no kernel: the runtime's copy engines move it between
+// the tensor and the host buffer, which costs kernels running beside it next to nothing.  Smaller
+// pieces are worth a copy of their own only when few of them lie together; a run of at least
+// gather_min consecutive small pieces inside one bucket is gathered into a staging slot by one
+// kernel launch and leaves as one copy (many small tensors would otherwise mean thousands of tiny
+// transfers).
+static void classify_pieces(const reft_plan *p, uint64_t bucket_begin, uint64_t bucket_end,
+                            std::vector<Run> &runs, std::vector<Dma> &dmas)
+{
+    const uint64_t dma_min = g_dma_min.load(), gather_min = g_gather_min.load();
+    std::vector<Dma> pending;
+    auto flush = [&]() {
+        if (pending.empty()) return;
+        if (pending.size() >= gather_min)
+            runs.push_back(Run{pending.front().o, pending.back().o + pending.back().n});
+        else
+            dmas.insert(dmas.end(), pending.begin(), pending.end());
+        pending.clear();
+    };
+    uint64_t i = 0;
+    for (uint64_t b = bucket_begin; b < bucket_end; ++b) {
+        const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
+        if (b == bucket_begin) {
+            // the span that owns byte lo: last one with off <= lo that is not empty
+            uint64_t l = 0, h = p->T;
+            while (h - l > 1) {
+                const uint64_t m = (l + h) / 2;
+                if (p->off[m] <= lo) l = m;
+                else h = m;
+            }
+            i = l;
+        }
+        for (uint64_t o = lo; o < hi;) {
+            while (p->off[i + 1] <= o) ++i;              // o < hi <= L = off[T]
+            const uint64_t pe = p->off[i + 1] < hi ? p->off[i + 1] : hi;
+            if (pe - o >= dma_min) {
+                flush();
+                dmas.push_back(Dma{o, pe - o, i});
+            } else {
+                pending.push_back(Dma{o, pe - o, i});
+            }
+            o = pe;
+        }
+        flush();                                         // a run never crosses a bucket
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // S1 + S2 + S3: snapshot
 // ------------------------------------------------------------------------------------------------
 static int staging_slots(const reft_plan *p, const void *staging, uint64_t staging_bytes,
@@ -491,42 +565,59 @@ extern "C" int reft_snapshot_pack_range(reft_plan *p, const void *const *span_pt
         return record(p->pack_done, ps);
     }
 
-    // Staged path: gather kernels fill staging slots, hipMemcpyAsync moves each bucket to the
-    // host.  The slots form two groups that alternate between the streams; the streams meet only
-    // once per group (cross-stream events are costly when thousands are in flight).
+    // Staged transport.  Large pieces go by DMA straight from their tensors; runs of small pieces
+    // are gathered into staging slots and leave as one copy each (see classify_pieces).  The slots
+    // form two groups that alternate between the streams; the streams meet only once per group
+    // (cross-stream events are costly when thousands are in flight).
     int nslots = 1;
     if ((rc = staging_slots(p, staging, staging_bytes, "reft_snapshot_pack", &nslots))) return rc;
-    if ((rc = upload_ptrs(p, span_ptrs, 1, ps, &tab, &entry))) return rc;
-    const LaunchCfg cfg = launch_cfg(p);
+    std::vector<Run> runs;
+    std::vector<Dma> dmas;
+    classify_pieces(p, bucket_begin, bucket_end, runs, dmas);
     const uint64_t stride = slot_stride(p);
-    const int ngroups = nslots >= kGroups ? kGroups : 1;
-    const uint64_t per_group = (uint64_t)(nslots / ngroups);
-    uint64_t batch = 0;
-    for (uint64_t b0 = bucket_begin; b0 < bucket_end; b0 += per_group, ++batch) {
-        const int g = (int)(batch % (uint64_t)ngroups);
-        const uint64_t b1 = b0 + per_group < bucket_end ? b0 + per_group : bucket_end;
-        // the group's previous occupants must have left for the host
-        if ((rc = wait_on(ps, p->pack_free[g]))) return rc;
-        for (uint64_t b = b0; b < b1; ++b) {
-            const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
-            const uint64_t slot = (uint64_t)g * per_group + (b - b0);
-            const uint64_t slot_addr = (uint64_t)(uintptr_t)staging + slot * stride + (lo & 255);
-            HIPCHK(launch_gather(pt, tab, 1, false, nullptr, slot_addr - lo, lo, hi, cfg, ps));
-        }
-        if ((rc = record(p->pack_filled[g], ps))) return rc;
-        if ((rc = wait_on(cs, p->pack_filled[g]))) return rc;
-        for (uint64_t b = b0; b < b1; ++b) {
-            const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
-            const uint64_t slot = (uint64_t)g * per_group + (b - b0);
-            const uint64_t slot_addr = (uint64_t)(uintptr_t)staging + slot * stride + (lo & 255);
-            HIPCHK(hipMemcpyAsync((uint8_t *)host_dst + lo, (const void *)(uintptr_t)slot_addr,
-                                  hi - lo, hipMemcpyDeviceToHost, cs));
-        }
-        if ((rc = record(p->pack_free[g], cs))) return rc;
+    // The tensors are read on both streams.  The caller orders pack_stream behind whatever
+    // produced them; copy_stream joins pack_stream here so the same ordering covers its copies.
+    if (ps != cs) {
+        if ((rc = record(p->pack_begin, ps))) return rc;
+        if ((rc = wait_on(cs, p->pack_begin))) return rc;
     }
-    if ((rc = record(p->ring_ev[entry], ps))) return rc;
-    // completion: all buckets have landed once copy_stream reaches this point
-    if ((rc = wait_on(cs, p->ring_ev[entry]))) return rc;
+    if (!runs.empty()) {
+        if ((rc = upload_ptrs(p, span_ptrs, 1, ps, &tab, &entry))) return rc;
+        const LaunchCfg cfg = launch_cfg(p);
+        const int ngroups = nslots >= kGroups ? kGroups : 1;
+        const uint64_t per_group = (uint64_t)(nslots / ngroups);
+        uint64_t batch = 0;
+        for (uint64_t r0 = 0; r0 < runs.size(); r0 += per_group, ++batch) {
+            const int g = (int)(batch % (uint64_t)ngroups);
+            const uint64_t r1 = r0 + per_group < runs.size() ? r0 + per_group : runs.size();
+            // the group's previous occupants must have left for the host
+            if ((rc = wait_on(ps, p->pack_free[g]))) return rc;
+            for (uint64_t r = r0; r < r1; ++r) {
+                const uint64_t slot = (uint64_t)g * per_group + (r - r0);
+                const uint64_t slot_addr =
+                    (uint64_t)(uintptr_t)staging + slot * stride + (runs[r].a & 255);
+                HIPCHK(launch_gather(pt, tab, 1, false, nullptr, slot_addr - runs[r].a, runs[r].a,
+                                     runs[r].b, cfg, ps));
+            }
+            if ((rc = record(p->pack_filled[g], ps))) return rc;
+            if ((rc = wait_on(cs, p->pack_filled[g]))) return rc;
+            for (uint64_t r = r0; r < r1; ++r) {
+                const uint64_t slot = (uint64_t)g * per_group + (r - r0);
+                const uint64_t slot_addr =
+                    (uint64_t)(uintptr_t)staging + slot * stride + (runs[r].a & 255);
+                HIPCHK(hipMemcpyAsync((uint8_t *)host_dst + runs[r].a,
+                                      (const void *)(uintptr_t)slot_addr, runs[r].b - runs[r].a,
+                                      hipMemcpyDeviceToHost, cs));
+            }
+            if ((rc = record(p->pack_free[g], cs))) return rc;
+        }
+        if ((rc = record(p->ring_ev[entry], ps))) return rc;
+    }
+    for (const Dma &d : dmas)
+        HIPCHK(hipMemcpyAsync((uint8_t *)host_dst + d.o,
+                              (const uint8_t *)span_ptrs[d.span] + (d.o - p->off[d.span]), d.n,
+                              hipMemcpyDeviceToHost, cs));
+    // completion: every copy above is on copy_stream, the gathered ones behind their kernels
     return record(p->pack_done, cs);
 }
 
@@ -888,35 +979,54 @@ extern "C" int reft_restore(reft_plan *p, const void *host_src, uint64_t host_by
 
     int nslots = 1;
     if ((rc = staging_slots(p, staging, staging_bytes, "reft_restore", &nslots))) return rc;
-    if ((rc = upload_ptrs(p, span_ptrs, 1, us, &tab, &entry))) return rc;
-    const LaunchCfg cfg = launch_cfg(p);
+    std::vector<Run> runs;
+    std::vector<Dma> dmas;
+    classify_pieces(p, 0, p->NB, runs, dmas);
     const uint64_t stride = slot_stride(p);
-    const int ngroups = nslots >= kGroups ? kGroups : 1;
-    const uint64_t per_group = (uint64_t)(nslots / ngroups);
-    uint64_t batch = 0;
-    for (uint64_t b0 = 0; b0 < p->NB; b0 += per_group, ++batch) {
-        const int g = (int)(batch % (uint64_t)ngroups);
-        const uint64_t b1 = b0 + per_group < p->NB ? b0 + per_group : p->NB;
-        // the group's previous occupants must have been scattered
-        if ((rc = wait_on(cs, p->rest_free[g]))) return rc;
-        for (uint64_t b = b0; b < b1; ++b) {
-            const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
-            const uint64_t slot = (uint64_t)g * per_group + (b - b0);
-            const uint64_t slot_addr = (uint64_t)(uintptr_t)staging + slot * stride + (lo & 255);
-            HIPCHK(hipMemcpyAsync((void *)(uintptr_t)slot_addr, (const uint8_t *)host_src + lo,
-                                  hi - lo, hipMemcpyHostToDevice, cs));
-        }
-        if ((rc = record(p->rest_filled[g], cs))) return rc;
-        if ((rc = wait_on(us, p->rest_filled[g]))) return rc;
-        for (uint64_t b = b0; b < b1; ++b) {
-            const uint64_t lo = p->bstart[b], hi = p->bstart[b + 1];
-            const uint64_t slot = (uint64_t)g * per_group + (b - b0);
-            const uint64_t slot_addr = (uint64_t)(uintptr_t)staging + slot * stride + (lo & 255);
-            HIPCHK(launch_scatter(pt, tab, slot_addr - lo, lo, hi, cfg, us));
-        }
-        if ((rc = record(p->rest_free[g], us))) return rc;
+    // The tensors are written on both streams.  The caller orders unpack_stream behind their last
+    // use; copy_stream joins unpack_stream here so the same ordering covers its copies.
+    if (us != cs) {
+        if ((rc = record(p->rest_begin, us))) return rc;
+        if ((rc = wait_on(cs, p->rest_begin))) return rc;
     }
-    if ((rc = record(p->ring_ev[entry], us))) return rc;
+    // large pieces: straight from the host snapshot into their tensors
+    for (const Dma &d : dmas)
+        HIPCHK(hipMemcpyAsync((uint8_t *)span_ptrs[d.span] + (d.o - p->off[d.span]),
+                              (const uint8_t *)host_src + d.o, d.n, hipMemcpyHostToDevice, cs));
+    if (!runs.empty()) {
+        if ((rc = upload_ptrs(p, span_ptrs, 1, us, &tab, &entry))) return rc;
+        const LaunchCfg cfg = launch_cfg(p);
+        const int ngroups = nslots >= kGroups ? kGroups : 1;
+        const uint64_t per_group = (uint64_t)(nslots / ngroups);
+        uint64_t batch = 0;
+        for (uint64_t r0 = 0; r0 < runs.size(); r0 += per_group, ++batch) {
+            const int g = (int)(batch % (uint64_t)ngroups);
+            const uint64_t r1 = r0 + per_group < runs.size() ? r0 + per_group : runs.size();
+            // the group's previous occupants must have been scattered
+            if ((rc = wait_on(cs, p->rest_free[g]))) return rc;
+            for (uint64_t r = r0; r < r1; ++r) {
+                const uint64_t slot = (uint64_t)g * per_group + (r - r0);
+                const uint64_t slot_addr =
+                    (uint64_t)(uintptr_t)staging + slot * stride + (runs[r].a & 255);
+                HIPCHK(hipMemcpyAsync((void *)(uintptr_t)slot_addr,
+                                      (const uint8_t *)host_src + runs[r].a, runs[r].b - runs[r].a,
+                                      hipMemcpyHostToDevice, cs));
+            }
+            if ((rc = record(p->rest_filled[g], cs))) return rc;
+            if ((rc = wait_on(us, p->rest_filled[g]))) return rc;
+            for (uint64_t r = r0; r < r1; ++r) {
+                const uint64_t slot = (uint64_t)g * per_group + (r - r0);
+                const uint64_t slot_addr =
+                    (uint64_t)(uintptr_t)staging + slot * stride + (runs[r].a & 255);
+                HIPCHK(launch_scatter(pt, tab, slot_addr - runs[r].a, runs[r].a, runs[r].b, cfg, us));
+            }
+            if ((rc = record(p->rest_free[g], us))) return rc;
+        }
+        if ((rc = record(p->ring_ev[entry], us))) return rc;
+    }
+    // completion on unpack_stream: behind the scatter kernels and behind every direct copy
+    if ((rc = record(p->rest_copied, cs))) return rc;
+    if ((rc = wait_on(us, p->rest_copied))) return rc;
     return record(p->rest_done, us);
 }
 

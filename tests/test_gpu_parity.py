@@ -29,15 +29,24 @@ def dev():
     return d
 
 
-@pytest.fixture(autouse=True, params=["direct", "staged", "direct-lds", "staged-lds"])
+@pytest.fixture(autouse=True, params=["direct", "staged", "staged-gather", "direct-lds",
+                                      "staged-gather-lds", "staged-tiny-dma"])
 def default_tunables(request):
-    """Every case runs with both host transports, and with the kernels' LDS-staged small-piece
-    path forced on for every tile ("-lds"; by default only tiles with many small spans take it).
-    Launch parameters are restored afterwards."""
+    """Every case runs with each host transport: direct (kernels touch pinned host memory),
+    staged (large pieces by DMA from the tensors, runs of small pieces through gather kernel and
+    staging ring), staged-gather (every byte through the gather kernel and the ring) and
+    staged-tiny-dma (every piece, however small, its own DMA copy); "-lds" forces the kernels'
+    LDS-staged small-piece path on for every tile.  Launch parameters are restored afterwards."""
     global DIRECT
-    names = ("max_wgs", "nontemporal", "unroll", "tile_shift", "link_wgs", "small_pieces")
+    names = ("max_wgs", "nontemporal", "unroll", "tile_shift", "link_wgs", "small_pieces",
+             "dma_min_bytes", "gather_min_pieces")
     saved = {n: reft.reft_get_tunable(n) for n in names}
     DIRECT = request.param.startswith("direct")
+    if "-gather" in request.param:
+        reft.reft_set_tunable("dma_min_bytes", 1 << 62)
+        reft.reft_set_tunable("gather_min_pieces", 1)
+    if "-tiny-dma" in request.param:
+        reft.reft_set_tunable("dma_min_bytes", 0)
     if request.param.endswith("-lds"):
         reft.reft_set_tunable("small_pieces", 0)
     yield
