@@ -73,6 +73,13 @@ def main() -> int:
                     help="also run one plain device-to-device copy of 1 GiB (torch), the kernel of "
                          "known size that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--no-stages", action="store_true", help="skip the per-stage measurements")
+    ap.add_argument("--has-demo", action="store_true",
+                    help="instead of the benchmark: run a synthetic pipeline-stage timeline (idle "
+                         "bubble, then a GEMM burst) with no snapshot, with the whole save phase "
+                         "beside compute, and with the bubble-aware split of Algorithm 1; prints "
+                         "one JSON line of iteration times")
+    ap.add_argument("--bubble-ms", type=float, default=100.0, help="--has-demo: bubble length")
+    ap.add_argument("--burst-gemms", type=int, default=800, help="--has-demo: GEMMs per iteration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-mib", type=int, default=2048,
                     help="bytes per shard of the CPU-oracle sample, MiB")
@@ -195,6 +202,14 @@ def main() -> int:
         done = torch.cuda.Event()
         done.record(s_xor)                      # the decode is the last thing a step does
         in_flight.append(done)
+
+    if args.has_demo:
+        rec = has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, host_snap,
+                       host_par, stag_save, stag_psave)
+        reft.reft_plan_destroy(plan)
+        reft.reft_plan_destroy(pplan)
+        print(json.dumps(rec), flush=True)
+        return 0
 
     if args.calibration_copy:
         a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(7)
@@ -395,6 +410,94 @@ def main() -> int:
     reft.reft_plan_destroy(pplan)
     print(json.dumps(record), flush=True)
     return 0 if verified else 1
+
+
+def has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, host_snap, host_par,
+             stag_save, stag_psave):
+    """Hierarchical scheduling of one snapshot per iteration on a synthetic pipeline-stage timeline
+    (Algorithm 1): each iteration is an idle bubble followed by a burst of bf16 GEMMs.
+
+      none   no snapshot.
+      naive  the whole save phase (encode, shard snapshot, parity snapshot; staged transport) is
+             launched with the burst and runs beside it.
+      has    layer 1: in the bubble, the parity encode and W_bubble = the buckets before the cut
+             floor(n * t_bubble / t_ss) (SplitParameter), sent with the direct transport at full
+             link rate; layer 2: the remaining buckets and the parity go out beside the burst with
+             the staged transport (DMA copies, no kernels).
+
+    t_ss = size / B_io (EstimateSnapshotTime) with B_io measured here; the bubble length is an
+    input (the printed EstimateBubbleTime formula is not used)."""
+    dev = torch.device("cuda:0")
+    n = 8192
+    A = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
+    B = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
+    C = torch.empty(n, n, device=dev, dtype=torch.bfloat16)
+    s_gemm, s_snap, s_copy, s_xor = (torch.cuda.Stream() for _ in range(4))
+    nb = reft.reft_plan_num_buckets(plan)
+    t_bubble = args.bubble_ms * 1e-3
+
+    # B_io: the direct transport's rate on this box
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    reft.reft_snapshot_pack(plan, p_own, None, host_snap, s_snap, None)
+    torch.cuda.synchronize()
+    b_io = L / (time.perf_counter() - t0)
+    t_ss = L / b_io
+    cut = reft.reft_plan_split(plan, 0.9 * t_bubble, t_ss)          # 10 % safety margin
+    b_cut = reft.reft_plan_bucket_of(plan, cut)
+
+    def burst():
+        with torch.cuda.stream(s_gemm):
+            for _ in range(args.burst_gemms):
+                torch.matmul(A, B, out=C)
+        ev = torch.cuda.Event()
+        ev.record(s_gemm)
+        return ev
+
+    def save_all_beside_compute():
+        reft.reft_parity_encode(plan, p_all, k, parity, s_xor)
+        reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_snap, s_copy)
+        s_snap.wait_stream(s_xor)
+        reft.reft_snapshot_pack(pplan, p_par, stag_psave, host_par, s_snap, s_copy)
+
+    def iteration(policy):
+        t_start = time.perf_counter()
+        if policy == "has":                      # layer 1: the bubble
+            reft.reft_parity_encode(plan, p_all, k, parity, s_xor)
+            reft.reft_snapshot_pack_range(plan, p_own, None, host_snap, 0, b_cut, s_snap, None)
+        while time.perf_counter() - t_start < t_bubble:
+            time.sleep(0.0005)
+        done = burst()
+        if policy == "naive":
+            save_all_beside_compute()
+        elif policy == "has":                    # layer 2: beside compute, copies only
+            reft.reft_snapshot_pack_range(plan, p_own, stag_save, host_snap, b_cut, nb, s_snap, s_copy)
+            s_snap.wait_stream(s_xor)
+            reft.reft_snapshot_pack(pplan, p_par, stag_psave, host_par, s_snap, s_copy)
+        done.synchronize()
+        t_compute_done = time.perf_counter()
+        torch.cuda.synchronize()                 # the snapshot must have landed before the next one
+        return t_compute_done - t_start, time.perf_counter() - t_start
+
+    out = {}
+    for policy in ("none", "naive", "has", "none", "naive", "has"):
+        iteration(policy)                        # warm-up
+        its = [iteration(policy) for _ in range(5)]
+        med = sorted(x[0] for x in its)[2]
+        full = sorted(x[1] for x in its)[2]
+        out.setdefault(policy, []).append((med, full))
+    res = {p: (min(v[0][0], v[1][0]), min(v[0][1], v[1][1])) for p, v in out.items()}
+    base = res["none"][0]
+    return {
+        "metric": "iteration time of a synthetic pipeline stage with one snapshot per iteration",
+        "workload": f"config {args.config}",
+        "bubble_ms": args.bubble_ms, "burst_gemms": args.burst_gemms,
+        "B_io_GBps": round(b_io / 1e9, 2), "t_ss_ms": round(t_ss * 1e3, 1),
+        "cut_bytes": cut, "cut_bucket": b_cut, "buckets": nb,
+        "iteration_ms": {p: round(v[0] * 1e3, 2) for p, v in res.items()},
+        "iteration_plus_snapshot_tail_ms": {p: round(v[1] * 1e3, 2) for p, v in res.items()},
+        "overhead_pct": {p: round(100.0 * (v[0] - base) / base, 2) for p, v in res.items()},
+    }
 
 
 def measured_traffic(cfg: int):

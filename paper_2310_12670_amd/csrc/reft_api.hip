@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <exception>
 #include <new>
 #include <vector>
 
@@ -26,6 +27,15 @@ static int fail(int code, const char *fmt, ...)
     va_end(ap);
     return code;
 }
+
+// Entry points that build host-side tables must not let an allocation failure escape the C ABI.
+#define REFT_GUARD_BEGIN try {
+#define REFT_GUARD_END(who)                                                                       \
+    }                                                                                             \
+    catch (const std::exception &e)                                                               \
+    {                                                                                             \
+        return fail(REFT_EINVAL, "%s: host allocation failed (%s)", who, e.what());               \
+    }
 
 #define HIPCHK(expr)                                                                              \
     do {                                                                                          \
@@ -261,6 +271,7 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
                                 const uint64_t *bucket_nbytes, uint64_t NB,
                                 uint64_t uniform_bucket, reft_plan **out)
 {
+    REFT_GUARD_BEGIN
     if (!out) return fail(REFT_EINVAL, "reft_plan_create: null out");
     *out = nullptr;
     if (!span_nbytes || T == 0) return fail(REFT_EINVAL, "reft_plan_create: no spans");
@@ -355,6 +366,7 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
     guard.p = nullptr;
     *out = p;
     return REFT_OK;
+    REFT_GUARD_END("reft_plan_create")
 }
 
 extern "C" void reft_plan_destroy(reft_plan *p)
@@ -533,6 +545,7 @@ extern "C" int reft_snapshot_pack_range(reft_plan *p, const void *const *span_pt
                                         uint64_t bucket_begin, uint64_t bucket_end,
                                         reft_stream pack_stream, reft_stream copy_stream)
 {
+    REFT_GUARD_BEGIN
     int rc = check_plan(p, "reft_snapshot_pack");
     if (rc) return rc;
     if (bucket_begin > bucket_end || bucket_end > p->NB)
@@ -619,6 +632,7 @@ extern "C" int reft_snapshot_pack_range(reft_plan *p, const void *const *span_pt
                               hipMemcpyDeviceToHost, cs));
     // completion: every copy above is on copy_stream, the gathered ones behind their kernels
     return record(p->pack_done, cs);
+    REFT_GUARD_END("reft_snapshot_pack")
 }
 
 extern "C" int reft_snapshot_pack(reft_plan *p, const void *const *span_ptrs, void *staging,
@@ -900,6 +914,7 @@ extern "C" int reft_reconstruct_spans(reft_plan *p, const void *const *shard_spa
                                       uint32_t lost, const void *parity_dev,
                                       void *const *out_span_ptrs, reft_stream stream)
 {
+    REFT_GUARD_BEGIN
     int rc = check_plan(p, "reft_reconstruct_spans");
     if (rc) return rc;
     if (k < 1 || k > REFT_MAX_K - 1)
@@ -942,6 +957,7 @@ extern "C" int reft_reconstruct_spans(reft_plan *p, const void *const *shard_spa
         done += n;
     }
     return record(p->ring_ev[entry], s);
+    REFT_GUARD_END("reft_reconstruct_spans")
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -951,6 +967,7 @@ extern "C" int reft_restore(reft_plan *p, const void *host_src, uint64_t host_by
                             uint64_t staging_bytes, void *const *span_ptrs,
                             reft_stream copy_stream, reft_stream unpack_stream)
 {
+    REFT_GUARD_BEGIN
     int rc = check_plan(p, "reft_restore");
     if (rc) return rc;
     if ((rc = check_span_ptrs(p, span_ptrs, 1, "reft_restore"))) return rc;
@@ -1028,6 +1045,7 @@ extern "C" int reft_restore(reft_plan *p, const void *host_src, uint64_t host_by
     if ((rc = record(p->rest_copied, cs))) return rc;
     if ((rc = wait_on(us, p->rest_copied))) return rc;
     return record(p->rest_done, us);
+    REFT_GUARD_END("reft_restore")
 }
 
 extern "C" int reft_restore_wait(reft_plan *p)
