@@ -242,7 +242,8 @@ int reft_restore_wait(reft_plan *plan);
  *                  a snapshot kernel on few compute units while training kernels run beside it.
  *   "nontemporal"  1 = streaming (non-temporal) loads and stores in the kernels, 0 = plain.
  *   "unroll"       16-byte chunks in flight per thread and source: 1, 2 or 4.
- *   "link_wgs"     cap on workgroups of kernels bound by the host link (default 32).
+ *   "link_wgs"     cap on workgroups of kernels bound by the host link (default 32; kernels
+ *                  that read host memory use twice this).
  *   "dma_min_bytes"     staged transport: pieces of at least this size travel by DMA alone
  *                  (default 65536; 0 = every piece; a huge value = none, everything is gathered).
  *   "gather_min_pieces" staged transport: shortest run of smaller pieces that is gathered by a

@@ -987,7 +987,8 @@ extern "C" int reft_restore(reft_plan *p, const void *host_src, uint64_t host_by
             return fail(REFT_EINVAL, "reft_restore: host buffer is not mapped for device access "
                                      "(not pinned); pass a staging ring to copy it by DMA");
         if ((rc = upload_ptrs(p, span_ptrs, 1, us, &tab, &entry))) return rc;
-        const LaunchCfg cfg = link_cfg(p);
+        LaunchCfg cfg = link_cfg(p);
+        cfg.max_wgs *= 2;          // reads across the link need about twice the waves of writes
         for (uint64_t b = 0; b < p->NB; ++b)
             HIPCHK(launch_scatter(pt, tab, hview, p->bstart[b], p->bstart[b + 1], cfg, us));
         if ((rc = record(p->ring_ev[entry], us))) return rc;
