@@ -61,6 +61,9 @@ def main() -> int:
                     help="start the load phase only when the whole save phase has landed (default: "
                          "the own shard's restore starts as soon as its snapshot is on the host, "
                          "beside the parity's snapshot, which uses the link's other direction)")
+    ap.add_argument("--dma-streams", type=int, default=0, choices=[0, 1, 2],
+                    help="staged transport: 2 = piece copies alternate with a helper stream "
+                         "(0 = library default)")
     ap.add_argument("--one-stream-save", action="store_true",
                     help="staged save: gather kernels and copies in order on one stream")
     ap.add_argument("--one-stream-load", action="store_true",
@@ -143,6 +146,8 @@ def main() -> int:
 
     if args.link_wgs:
         reft.reft_set_tunable("link_wgs", args.link_wgs)
+    if args.dma_streams:
+        reft.reft_set_tunable("dma_streams", args.dma_streams)
     # s_snap / s_load carry the link-bound work (and, staged, the gather / scatter kernels);
     # s_copy / s_h2d carry the DMA transfers of the staged path; s_xor the HBM-bound XOR kernels.
     s_snap, s_xor, s_load = (torch.cuda.Stream() for _ in range(3))

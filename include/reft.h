@@ -248,6 +248,12 @@ int reft_restore_wait(reft_plan *plan);
  *                  (default 65536; 0 = every piece; a huge value = none, everything is gathered).
  *   "gather_min_pieces" staged transport: shortest run of smaller pieces that is gathered by a
  *                  kernel instead of being copied piece by piece (default 8, at least 1).
+ *   "dma_streams"  staged transport: 1 (default) = all piece copies on copy_stream; 2 = they
+ *                  alternate between copy_stream and a helper stream owned by the plan (forked from
+ *                  and joined to copy_stream, default priority), which hides the set-up gap between
+ *                  consecutive copies (53.8 -> 56.7 GB/s) - but only while the process has a free
+ *                  hardware queue for it: with more active streams than hardware queues (4 by
+ *                  default) the helper shares a queue and the snapshot gets slower instead.
  *   "small_pieces" a tile in which at least this many spans start is processed by the LDS-staged
  *                  small-piece path of the gather / scatter kernels (default 8; 4294967295 = never,
  *                  0 = always).

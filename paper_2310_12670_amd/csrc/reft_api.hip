@@ -54,6 +54,7 @@ static std::atomic<uint64_t> g_link_wgs{32};     // grid cap of kernels bound by
 static std::atomic<uint64_t> g_small_pieces{8}; // spans starting in a tile that switch it to LDS mode
 static std::atomic<uint64_t> g_dma_min{65536};   // pieces of at least this many bytes are copied by DMA
 static std::atomic<uint64_t> g_gather_min{8};    // shortest run of smaller pieces worth a gather kernel
+static std::atomic<uint64_t> g_dma_streams{1};   // 2 = piece copies alternate with a helper stream
 
 extern "C" int reft_set_tunable(const char *name, uint64_t value)
 {
@@ -76,6 +77,9 @@ extern "C" int reft_set_tunable(const char *name, uint64_t value)
         g_link_wgs = value;
     } else if (!strcmp(name, "dma_min_bytes")) {
         g_dma_min = value;
+    } else if (!strcmp(name, "dma_streams")) {
+        if (value < 1 || value > 2) return fail(REFT_EINVAL, "dma_streams must be 1 or 2");
+        g_dma_streams = value;
     } else if (!strcmp(name, "gather_min_pieces")) {
         if (value < 1) return fail(REFT_EINVAL, "gather_min_pieces must be at least 1");
         g_gather_min = value;
@@ -103,6 +107,7 @@ extern "C" int reft_get_tunable(const char *name, uint64_t *value)
     else if (!strcmp(name, "small_pieces")) *value = g_small_pieces;
     else if (!strcmp(name, "dma_min_bytes")) *value = g_dma_min;
     else if (!strcmp(name, "gather_min_pieces")) *value = g_gather_min;
+    else if (!strcmp(name, "dma_streams")) *value = g_dma_streams;
     else return fail(REFT_EINVAL, "unknown tunable '%s'", name);
     return REFT_OK;
 }
@@ -145,6 +150,10 @@ struct reft_plan {
     // bucket pipelines
     Event pack_filled[kGroups], pack_free[kGroups], pack_done, pack_begin, rest_begin;
     Event rest_filled[kGroups], rest_free[kGroups], rest_done, rest_copied;
+    // helper stream for the staged transport's piece copies (tunable "dma_streams"), created on
+    // first use at the default priority, and the events that fork it from / join it to copy_stream
+    hipStream_t aux = nullptr;
+    Event aux_fork, aux_join;
 
     PlanTables tables() const { return PlanTables{d_off, d_first, T, L, tile_shift}; }
 };
@@ -359,7 +368,8 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
     }
     if ((rc = make_event(p->pack_done)) || (rc = make_event(p->rest_done)) ||
         (rc = make_event(p->rest_copied)) || (rc = make_event(p->pack_begin)) ||
-        (rc = make_event(p->rest_begin)))
+        (rc = make_event(p->rest_begin)) || (rc = make_event(p->aux_fork)) ||
+        (rc = make_event(p->aux_join)))
         return rc;
     if ((rc = ensure_ring(p, 8))) return rc;
 
@@ -390,6 +400,9 @@ extern "C" void reft_plan_destroy(reft_plan *p)
     drain(p->pack_done);
     drain(p->rest_done);
     drain(p->rest_copied);
+    drain(p->aux_fork);
+    drain(p->aux_join);
+    if (p->aux) (void)hipStreamDestroy(p->aux);
     drain(p->pack_begin);
     drain(p->rest_begin);
     free_ring(p);
@@ -519,6 +532,27 @@ static void classify_pieces(const reft_plan *p, uint64_t bucket_begin, uint64_t 
     }
 }
 
+// Issue the piece copies on copy_stream, or alternately on copy_stream and the plan's helper
+// stream (forked from and joined back to copy_stream, so ordering on copy_stream still covers
+// every copy): two queues hide the set-up gap between consecutive small copies.
+template <typename Issue>
+static int issue_piece_copies(reft_plan *p, const std::vector<Dma> &dmas, hipStream_t cs, Issue issue)
+{
+    int rc;
+    const bool two = g_dma_streams.load() == 2 && dmas.size() >= 4;
+    if (two) {
+        if (!p->aux) HIPCHK(hipStreamCreateWithFlags(&p->aux, hipStreamNonBlocking));
+        if ((rc = record(p->aux_fork, cs))) return rc;
+        if ((rc = wait_on(p->aux, p->aux_fork))) return rc;
+    }
+    for (size_t i = 0; i < dmas.size(); ++i) HIPCHK(issue(dmas[i], (two && (i & 1)) ? p->aux : cs));
+    if (two) {
+        if ((rc = record(p->aux_join, p->aux))) return rc;
+        if ((rc = wait_on(cs, p->aux_join))) return rc;
+    }
+    return REFT_OK;
+}
+
 // ------------------------------------------------------------------------------------------------
 // S1 + S2 + S3: snapshot
 // ------------------------------------------------------------------------------------------------
@@ -626,10 +660,12 @@ extern "C" int reft_snapshot_pack_range(reft_plan *p, const void *const *span_pt
         }
         if ((rc = record(p->ring_ev[entry], ps))) return rc;
     }
-    for (const Dma &d : dmas)
-        HIPCHK(hipMemcpyAsync((uint8_t *)host_dst + d.o,
-                              (const uint8_t *)span_ptrs[d.span] + (d.o - p->off[d.span]), d.n,
-                              hipMemcpyDeviceToHost, cs));
+    if ((rc = issue_piece_copies(p, dmas, cs, [&](const Dma &d, hipStream_t st) {
+            return hipMemcpyAsync((uint8_t *)host_dst + d.o,
+                                  (const uint8_t *)span_ptrs[d.span] + (d.o - p->off[d.span]), d.n,
+                                  hipMemcpyDeviceToHost, st);
+        })))
+        return rc;
     // completion: every copy above is on copy_stream, the gathered ones behind their kernels
     return record(p->pack_done, cs);
     REFT_GUARD_END("reft_snapshot_pack")
@@ -1008,9 +1044,11 @@ extern "C" int reft_restore(reft_plan *p, const void *host_src, uint64_t host_by
         if ((rc = wait_on(cs, p->rest_begin))) return rc;
     }
     // large pieces: straight from the host snapshot into their tensors
-    for (const Dma &d : dmas)
-        HIPCHK(hipMemcpyAsync((uint8_t *)span_ptrs[d.span] + (d.o - p->off[d.span]),
-                              (const uint8_t *)host_src + d.o, d.n, hipMemcpyHostToDevice, cs));
+    if ((rc = issue_piece_copies(p, dmas, cs, [&](const Dma &d, hipStream_t st) {
+            return hipMemcpyAsync((uint8_t *)span_ptrs[d.span] + (d.o - p->off[d.span]),
+                                  (const uint8_t *)host_src + d.o, d.n, hipMemcpyHostToDevice, st);
+        })))
+        return rc;
     if (!runs.empty()) {
         if ((rc = upload_ptrs(p, span_ptrs, 1, us, &tab, &entry))) return rc;
         const LaunchCfg cfg = launch_cfg(p);

@@ -39,7 +39,7 @@ def default_tunables(request):
     LDS-staged small-piece path on for every tile.  Launch parameters are restored afterwards."""
     global DIRECT
     names = ("max_wgs", "nontemporal", "unroll", "tile_shift", "link_wgs", "small_pieces",
-             "dma_min_bytes", "gather_min_pieces")
+             "dma_min_bytes", "gather_min_pieces", "dma_streams")
     saved = {n: reft.reft_get_tunable(n) for n in names}
     DIRECT = request.param.startswith("direct")
     if "-gather" in request.param:
@@ -47,6 +47,7 @@ def default_tunables(request):
         reft.reft_set_tunable("gather_min_pieces", 1)
     if "-tiny-dma" in request.param:
         reft.reft_set_tunable("dma_min_bytes", 0)
+        reft.reft_set_tunable("dma_streams", 1)
     if request.param.endswith("-lds"):
         reft.reft_set_tunable("small_pieces", 0)
     yield
