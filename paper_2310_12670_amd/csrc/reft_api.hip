@@ -119,7 +119,7 @@ extern "C" const char *reft_version(void) { return "libreft 0.1 (gfx950)"; }
 // plan
 // ------------------------------------------------------------------------------------------------
 namespace {
-constexpr int kRing = 4;        // pointer-table uploads that may be in flight at once
+constexpr int kRing = 16;       // pointer-table uploads that may be in flight at once
 constexpr int kMaxSlots = 64;   // staging slots used by the staged bucket pipelines
 constexpr int kGroups = 2;      // the slots form two groups that alternate (double buffering)
 
