@@ -81,6 +81,8 @@ def main() -> int:
                          "bubble, then a GEMM burst) with no snapshot, with the whole save phase "
                          "beside compute, and with the bubble-aware split of Algorithm 1; prints "
                          "one JSON line of iteration times")
+    ap.add_argument("--no-has", action="store_true",
+                    help="skip the short stage-timeline run whose result goes into the record")
     ap.add_argument("--bubble-ms", type=float, default=100.0, help="--has-demo: bubble length")
     ap.add_argument("--burst-gemms", type=int, default=800, help="--has-demo: GEMMs per iteration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -196,6 +198,14 @@ def main() -> int:
         s_snap.wait_stream(s_xor)
         s_snap.wait_stream(s_load)
 
+    if args.has_demo:
+        rec = has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, host_snap,
+                       host_par, stag_save, stag_psave, s_snap, s_copy, s_xor)
+        reft.reft_plan_destroy(plan)
+        reft.reft_plan_destroy(pplan)
+        print(json.dumps(rec), flush=True)
+        return 0
+
     in_flight = []
 
     def step(timed=False):
@@ -207,14 +217,6 @@ def main() -> int:
         done = torch.cuda.Event()
         done.record(s_xor)                      # the decode is the last thing a step does
         in_flight.append(done)
-
-    if args.has_demo:
-        rec = has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, host_snap,
-                       host_par, stag_save, stag_psave)
-        reft.reft_plan_destroy(plan)
-        reft.reft_plan_destroy(pplan)
-        print(json.dumps(rec), flush=True)
-        return 0
 
     if args.calibration_copy:
         a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(7)
@@ -363,6 +365,12 @@ def main() -> int:
         }
         del A, B, C
 
+    # ---- bubble-aware scheduling of the save phase on a synthetic stage timeline ------------------
+    has = None
+    if save_staged and not args.no_has and args.gemm_seconds >= 0:
+        has = has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, host_snap,
+                       host_par, stag_save, stag_psave, s_snap, s_copy, s_xor, iterations=3)
+
     # ---- the CPU oracle on a bounded sample of the same workload --------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -409,6 +417,7 @@ def main() -> int:
         },
         "stages": stages,
         "gemm_proxy": gemm,
+        "stage_timeline": has,
         "cpu_baseline": cpu,
     }
     reft.reft_plan_destroy(plan)
@@ -418,7 +427,7 @@ def main() -> int:
 
 
 def has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, host_snap, host_par,
-             stag_save, stag_psave):
+             stag_save, stag_psave, s_snap, s_copy, s_xor, iterations=5):
     """Hierarchical scheduling of one snapshot per iteration on a synthetic pipeline-stage timeline
     (Algorithm 1): each iteration is an idle bubble followed by a burst of bf16 GEMMs.
 
@@ -437,11 +446,12 @@ def has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, 
     A = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
     B = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
     C = torch.empty(n, n, device=dev, dtype=torch.bfloat16)
-    s_gemm, s_snap, s_copy, s_xor = (torch.cuda.Stream() for _ in range(4))
+    s_gemm = torch.cuda.current_stream()
     nb = reft.reft_plan_num_buckets(plan)
     t_bubble = args.bubble_ms * 1e-3
 
     # B_io: the direct transport's rate on this machine
+    reft.reft_snapshot_pack(plan, p_own, None, host_snap, s_snap, None)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     reft.reft_snapshot_pack(plan, p_own, None, host_snap, s_snap, None)
@@ -487,9 +497,9 @@ def has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, 
     out = {}
     for policy in ("none", "naive", "has", "none", "naive", "has"):
         iteration(policy)                        # warm-up
-        its = [iteration(policy) for _ in range(5)]
-        med = sorted(x[0] for x in its)[2]
-        full = sorted(x[1] for x in its)[2]
+        its = [iteration(policy) for _ in range(iterations)]
+        med = sorted(x[0] for x in its)[len(its) // 2]
+        full = sorted(x[1] for x in its)[len(its) // 2]
         out.setdefault(policy, []).append((med, full))
     res = {p: (min(v[0][0], v[1][0]), min(v[0][1], v[1][1])) for p, v in out.items()}
     base = res["none"][0]
