@@ -48,6 +48,10 @@ class Oracle:
         lib.oracle_encode.argtypes = [p, u32, u64, p]
         lib.oracle_encode_padded.argtypes = [p, p, u32, p, u64]
         lib.oracle_reconstruct.argtypes = [p, u32, p, u64, p]
+        lib.oracle_segment_bytes.argtypes = [u64, u32]
+        lib.oracle_segment_bytes.restype = u64
+        lib.oracle_encode_rotated.argtypes = [p, u32, u64, u32, p]
+        lib.oracle_reconstruct_rotated.argtypes = [p, p, u32, u64, u32, p]
         self.lib = lib
 
     # -- threads for the optional outer-range split ------------------------------------------
@@ -113,6 +117,33 @@ class Oracle:
         return out
 
 
+    # -- rotated placement of the parity (section 4.2) ------------------------------------------
+    def segment_bytes(self, L: int, k: int) -> int:
+        return int(self.lib.oracle_segment_bytes(int(L), int(k)))
+
+    def encode_rotated(self, shards: Sequence[np.ndarray], member: int) -> np.ndarray:
+        L, k = shards[0].size, len(shards)
+        if any(s.size != L for s in shards):
+            raise ValueError("oracle: encode_rotated needs equal-length shards")
+        out = np.empty(self.segment_bytes(L, k) if k >= 2 else 0, dtype=np.uint8)
+        _check(self.lib.oracle_encode_rotated(_ptr_array(shards), k, L, int(member),
+                                              out.ctypes.data), "encode_rotated")
+        return out
+
+    def reconstruct_rotated(self, shards: Sequence[Optional[np.ndarray]],
+                            parities: Sequence[Optional[np.ndarray]], lost: int, L: int) -> np.ndarray:
+        """``shards[lost]`` and ``parities[lost]`` may be None: they are never read."""
+        k = len(shards)
+        dummy = np.zeros(1, dtype=np.uint8)
+        sh = [dummy if (a is None) else a for a in shards]
+        pa = [dummy if (a is None) else a for a in parities]
+        out = np.empty(L, dtype=np.uint8)
+        _check(self.lib.oracle_reconstruct_rotated(_ptr_array(sh), _ptr_array(pa), k, int(L),
+                                                   int(lost), out.ctypes.data),
+               "reconstruct_rotated")
+        return out
+
+
 # ------------------------------------------------------------------------------------------------
 # marshalling helpers (no arithmetic)
 # ------------------------------------------------------------------------------------------------
@@ -160,3 +191,8 @@ def unpack(stream, sizes):   return default().unpack(stream, sizes)
 def encode(shards):          return default().encode(shards)
 def encode_padded(shards):   return default().encode_padded(shards)
 def reconstruct(surv, par):  return default().reconstruct(surv, par)
+def segment_bytes(L, k):     return default().segment_bytes(L, k)
+def encode_rotated(shards, member):
+    return default().encode_rotated(shards, member)
+def reconstruct_rotated(shards, parities, lost, L):
+    return default().reconstruct_rotated(shards, parities, lost, L)

@@ -163,3 +163,71 @@ int oracle_reconstruct(const uint8_t *const *survivors, uint32_t n_survivors,
     }
     return 0;
 }
+
+/*
+ * Rotated placement of the parity (section 4.2, AEC): with m = k members in a sharding group,
+ * each member's shard is cut into k-1 segments and each member stores the parity of ONE segment
+ * of every OTHER member, so that every segment of every shard is protected exactly once and the
+ * redundancy per member is its shard size / (k-1) (the paper's W_n / (m (m-1)) with W_n / m the
+ * shard).  Eq. 1 gives the first member's unit: p_bcd0 = b_0 xor c_0 xor d_0.
+ *
+ * Reading taken for the general member i (the figure that shows it is not available): member i
+ * protects, from shard j != i, the segment with index r(i, j) = i if i < j, else i - 1.  For i = 0
+ * this is Eq. 1 literally (segment 0 of every other member); for a fixed j the indices r(i, j),
+ * i != j, are 0 .. k-2, each once.
+ *
+ * Segments have Lseg = ceil(L / (k-1)) bytes; the last one is zero-extended (0 is the identity of
+ * XOR).  k >= 2.  parity has Lseg bytes.
+ */
+uint64_t oracle_segment_bytes(uint64_t L, uint32_t k)
+{
+    return k < 2 ? 0 : (L + (k - 2)) / (k - 1);
+}
+
+static uint32_t oracle_rot_index(uint32_t i, uint32_t j) { return i < j ? i : i - 1; }
+
+int oracle_encode_rotated(const uint8_t *const *shards, uint32_t k, uint64_t L, uint32_t member,
+                          uint8_t *parity)
+{
+    if (k < 2 || member >= k) return -1;
+    const uint64_t Lseg = oracle_segment_bytes(L, k);
+    for (uint64_t x = 0; x < Lseg; ++x) {
+        uint8_t p = 0;
+        for (uint32_t j = 0; j < k; ++j) {
+            if (j == member) continue;
+            const uint64_t y = (uint64_t)oracle_rot_index(member, j) * Lseg + x;
+            if (y < L) p ^= shards[j][y];
+        }
+        parity[x] = p;
+    }
+    return 0;
+}
+
+/*
+ * Decode of a lost member (Eq. 2, the subtraction decoder, applied segment by segment): segment r
+ * of the lost shard is protected by the member i with r(i, lost) = r; it equals that member's
+ * parity unit xor the segments the unit also covers.  shards[lost] and parities[lost] are not
+ * read (they were on the lost node).  out has L bytes.
+ */
+int oracle_reconstruct_rotated(const uint8_t *const *shards, const uint8_t *const *parities,
+                               uint32_t k, uint64_t L, uint32_t lost, uint8_t *out)
+{
+    if (k < 2 || lost >= k) return -1;
+    const uint64_t Lseg = oracle_segment_bytes(L, k);
+    for (uint32_t r = 0; r + 1 < k; ++r) {
+        const uint32_t i = r < lost ? r : r + 1;         /* the member with r(i, lost) == r */
+        for (uint64_t x = 0; x < Lseg; ++x) {
+            const uint64_t o = (uint64_t)r * Lseg + x;
+            if (o >= L) break;
+            uint8_t v = parities[i][x];
+            for (uint32_t j = 0; j < k; ++j) {
+                if (j == i || j == lost) continue;
+                const uint64_t y = (uint64_t)oracle_rot_index(i, j) * Lseg + x;
+                if (y < L) v ^= shards[j][y];
+            }
+            out[o] = v;
+        }
+    }
+    return 0;
+}
+

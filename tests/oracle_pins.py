@@ -255,7 +255,106 @@ def pin_rejects(orc):
         raise AssertionError("unpack accepted sizes that do not sum to the stream length")
 
 
+# ------------------------------------------------------------------------------------------------
+# rotated placement of the parity (section 4.2)
+# ------------------------------------------------------------------------------------------------
+def _segments(shard, k):
+    """The k-1 zero-extended segments of a shard, by numpy slicing."""
+    L = shard.size
+    Lseg = -(-L // (k - 1))
+    padded = np.concatenate([shard, np.zeros((k - 1) * Lseg - L, np.uint8)])
+    return padded.reshape(k - 1, Lseg) if Lseg else np.zeros((k - 1, 0), np.uint8)
+
+
+def pin_golden_rotated(orc):
+    """Eq. 1 for the first member and the hand-worked units of the others."""
+    rows = _read_golden("rotated_parity_worked.txt")
+    shards = [_hex(t) for k, t in rows if k == "shard"]
+    parities = [_hex(t) for k, t in rows if k == "parity"]
+    k, L = len(shards), shards[0].size
+    for i in range(k):
+        assert np.array_equal(orc.encode_rotated(shards, i), parities[i]), i
+    for lost in range(k):
+        sh = [None if j == lost else shards[j] for j in range(k)]
+        pa = [None if j == lost else parities[j] for j in range(k)]
+        assert np.array_equal(orc.reconstruct_rotated(sh, pa, lost, L), shards[lost]), lost
+
+
+def pin_rotated_invariants(orc):
+    rng = np.random.default_rng(31)
+    for k in (2, 3, 4, 5, 8):
+        for L in (0, 1, 6, 7, 41, 42, 43, 1000, 4099):
+            shards = [_rand(rng, L) for _ in range(k)]
+            parities = [orc.encode_rotated(shards, i) for i in range(k)]
+            Lseg = -(-L // (k - 1))
+            # redundancy per member = shard size / (k-1), rounded up
+            assert all(p.size == Lseg == orc.segment_bytes(L, k) for p in parities), (k, L)
+            segs = [_segments(s, k) for s in shards]
+            # Eq. 1 literally: the first member's unit is segment 0 of every other member
+            want0 = np.zeros(Lseg, np.uint8)
+            for j in range(1, k):
+                want0 ^= segs[j][0]
+            assert np.array_equal(parities[0], want0), (k, L)
+            # every segment of every shard is protected exactly once: the XOR of all units equals
+            # the XOR of all segments of all shards
+            allp = np.zeros(Lseg, np.uint8)
+            for p in parities:
+                allp ^= p
+            alls = np.zeros(Lseg, np.uint8)
+            for sg in segs:
+                for r in range(k - 1):
+                    alls ^= sg[r]
+            assert np.array_equal(allp, alls), (k, L)
+            # a unit never covers its own member: changing shard i leaves unit i unchanged
+            for i in (0, k - 1):
+                mod = [s.copy() for s in shards]
+                if L:
+                    mod[i] ^= 0xFF
+                assert np.array_equal(orc.encode_rotated(mod, i), parities[i]), (k, L, i)
+            # any one member lost: decoded from the others alone (its own data poisoned)
+            for lost in range(k):
+                sh = [(_rand(rng, L) if j == lost else shards[j]) for j in range(k)]
+                pa = [(_rand(rng, Lseg) if j == lost else parities[j]) for j in range(k)]
+                assert np.array_equal(orc.reconstruct_rotated(sh, pa, lost, L), shards[lost]), \
+                    (k, L, lost)
+    # two members: the unit of one is the other's whole shard (erasure coding degenerates to the
+    # redundant copy of ARC)
+    a, b = _rand(rng, 77), _rand(rng, 77)
+    assert np.array_equal(orc.encode_rotated([a, b], 0), b)
+    assert np.array_equal(orc.encode_rotated([a, b], 1), a)
+
+
+def pin_rotated_bruteforce(orc):
+    """Pure-Python loops over every byte, with the segment map written as a table."""
+    rng = np.random.default_rng(37)
+    for k in (3, 4):
+        # table[i][j] = segment of shard j protected on member i, built from the two rules
+        # "first member takes segment 0 of all" and "each (j, r) once", filled greedily
+        table = [[None] * k for _ in range(k)]
+        for j in range(k):
+            r = 0
+            for i in range(k):
+                if i != j:
+                    table[i][j] = r
+                    r += 1
+        for L in (5, 12, 13):
+            shards = [_rand(rng, L).tolist() for _ in range(k)]
+            Lseg = -(-L // (k - 1))
+            for i in range(k):
+                unit = []
+                for x in range(Lseg):
+                    v = 0
+                    for j in range(k):
+                        if j != i:
+                            y = table[i][j] * Lseg + x
+                            if y < L:
+                                v ^= shards[j][y]
+                    unit.append(v)
+                got = orc.encode_rotated([np.array(s, np.uint8) for s in shards], i)
+                assert got.tolist() == unit, (k, L, i)
+
+
 ALL_PINS = [pin_golden_xor, pin_golden_pack, pin_closed_form_parity, pin_closed_form_pack,
             pin_zero_sum, pin_round_trip_and_bucket_independence, pin_bruteforce_reconstruct,
             pin_special_cases, pin_linearity_and_word_width, pin_float_payloads, pin_padded,
-            pin_rejects]
+            pin_rejects, pin_golden_rotated, pin_rotated_invariants, pin_rotated_bruteforce]

@@ -41,6 +41,14 @@ MUTANTS = {
                  "        o += n + (n > 200);\n    }\n    return 0;\n}\n\n/*\n * The bucketed"),
     # unpack slices from the wrong offset
     "unpack_offset": ("dst[i] = stream[o + i];", "dst[i] = stream[o + i + (t > 2)];"),
+    # rotated placement: every member takes segment 0 (Eq. 1 applied to all members alike)
+    "rotated_all_segment0": ("static uint32_t oracle_rot_index(uint32_t i, uint32_t j) { return i < j ? i : i - 1; }",
+                             "static uint32_t oracle_rot_index(uint32_t i, uint32_t j) { (void)i; (void)j; return 0; }"),
+    # rotated placement: the other rotation (index by the protected shard, not by the member)
+    "rotated_transposed": ("static uint32_t oracle_rot_index(uint32_t i, uint32_t j) { return i < j ? i : i - 1; }",
+                           "static uint32_t oracle_rot_index(uint32_t i, uint32_t j) { return j < i ? j : j - 1; }"),
+    # rotated placement: the zero-extension of the last segment forgotten (reads past the shard)
+    "rotated_decode_skips_member": ("if (j == i || j == lost) continue;", "if (j == lost) continue;"),
     # padded encode ignores the lengths
     "padded_ignores_len": ("p ^= (i < lens[s]) ? shards[s][i] : 0;",
                            "p ^= (i < lens[0]) ? shards[s][i < lens[s] ? i : 0] : 0;"),
