@@ -224,6 +224,36 @@ int reft_reconstruct_spans(reft_plan *plan, const void *const *shard_span_ptrs, 
                            uint32_t lost, const void *parity_dev, void *const *out_span_ptrs,
                            reft_stream stream);
 
+/* ---- rotated placement of the parity (section 4.2, AEC) -------------------------------------------
+ * The paper's layout of the redundancy: each of the k members of a group cuts its shard into k-1
+ * segments of Lseg = ceil(L / (k-1)) bytes (the last one zero-extended) and stores the parity of
+ * ONE segment of every OTHER member, so that every segment of every shard is protected exactly
+ * once and each member holds shard / (k-1) bytes of redundancy (the paper's W_n / (m (m-1))).
+ * Member i protects, from shard j != i, segment r(i, j) = i if i < j, else i - 1; for the first
+ * member this is Eq. 1 literally (p_bcd0 = b_0 xor c_0 xor d_0).  The figure that shows the
+ * layout for the other members is not available; this is the reading taken.
+ *
+ * reft_segment_bytes            Lseg for this plan and k (0 if k < 2).
+ * reft_parity_encode_rotated    parity_dev[0..Lseg) = XOR over j != member of segment r(member, j)
+ *                               of shard j, read in place through the span pointers (row `member`
+ *                               of shard_span_ptrs is ignored).
+ * reft_reconstruct_rotated      decodes the lost member's shard into out_span_ptrs, segment by
+ *                               segment (Eq. 2): segment r is protected by the member i with
+ *                               r(i, lost) = r and equals parity_ptrs[i] xor the other segments
+ *                               that unit covers.  Row `lost` of shard_span_ptrs and entry `lost`
+ *                               of parity_ptrs are ignored (they were on the lost node);
+ *                               parity_ptrs[i] are device pointers to Lseg bytes each.
+ * 2 <= k <= REFT_MAX_K.  The first call for a given (k, member) or (k, lost) builds and caches
+ * derived tables in the plan (allocates); later calls do not.
+ * Errors: REFT_EINVAL (k, member or lost out of range, null pointers), REFT_EHIP.
+ */
+uint64_t reft_segment_bytes(const reft_plan *plan, uint32_t k);
+int reft_parity_encode_rotated(reft_plan *plan, const void *const *shard_span_ptrs, uint32_t k,
+                               uint32_t member, void *parity_dev, reft_stream stream);
+int reft_reconstruct_rotated(reft_plan *plan, const void *const *shard_span_ptrs,
+                             const void *const *parity_ptrs, uint32_t k, uint32_t lost,
+                             void *const *out_span_ptrs, reft_stream stream);
+
 /* ---- S5 + S7: load a shard from pinned host memory back into its tensors (section 4.3, step 1) ---
  * The inverse of reft_snapshot_pack, with the same two transports: staged (staging != NULL:
  * large pieces by hipMemcpyAsync on copy_stream straight into their tensors, runs of small pieces

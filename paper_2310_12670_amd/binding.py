@@ -23,7 +23,8 @@ __all__ = [
     "reft_snapshot_query", "reft_ckpt_create", "reft_ckpt_destroy", "reft_ckpt_begin",
     "reft_ckpt_commit", "reft_ckpt_latest",
     "reft_pack_device", "reft_unpack_device", "reft_parity_encode", "reft_reconstruct",
-    "reft_reconstruct_spans", "reft_restore", "reft_restore_wait",
+    "reft_reconstruct_spans", "reft_segment_bytes", "reft_parity_encode_rotated",
+    "reft_reconstruct_rotated", "reft_restore", "reft_restore_wait",
     "reft_set_tunable", "reft_get_tunable", "reft_last_error", "reft_version",
 ]
 
@@ -85,6 +86,9 @@ def _load():
         "reft_parity_encode": (i, [vp, vp, u32, vp, vp]),
         "reft_reconstruct": (i, [vp, u32, vp, u64, vp, ctypes.POINTER(u32), vp]),
         "reft_reconstruct_spans": (i, [vp, vp, u32, u32, vp, vp, vp]),
+        "reft_segment_bytes": (u64, [vp, u32]),
+        "reft_parity_encode_rotated": (i, [vp, vp, u32, u32, vp, vp]),
+        "reft_reconstruct_rotated": (i, [vp, vp, vp, u32, u32, vp, vp]),
         "reft_restore": (i, [vp, vp, u64, vp, u64, vp, vp, vp]),
         "reft_restore_wait": (i, [vp]),
         "reft_set_tunable": (i, [ctypes.c_char_p, u64]),
@@ -313,6 +317,23 @@ def reft_reconstruct_spans(plan, shard_span_ptrs, k: int, lost: int, parity_dev,
     _check(_load().reft_reconstruct_spans(plan, ptr_array(shard_span_ptrs), int(k), int(lost),
                                           _addr(parity_dev), ptr_array(out_span_ptrs),
                                           _stream(stream)))
+
+
+def reft_segment_bytes(plan, k: int) -> int:
+    return int(_load().reft_segment_bytes(plan, int(k)))
+
+
+def reft_parity_encode_rotated(plan, shard_span_ptrs, k: int, member: int, parity_dev,
+                               stream=None) -> None:
+    _check(_load().reft_parity_encode_rotated(plan, ptr_array(shard_span_ptrs), int(k), int(member),
+                                              _addr(parity_dev), _stream(stream)))
+
+
+def reft_reconstruct_rotated(plan, shard_span_ptrs, parity_ptrs, k: int, lost: int, out_span_ptrs,
+                             stream=None) -> None:
+    _check(_load().reft_reconstruct_rotated(plan, ptr_array(shard_span_ptrs), ptr_array(parity_ptrs),
+                                            int(k), int(lost), ptr_array(out_span_ptrs),
+                                            _stream(stream)))
 
 
 def reft_restore(plan, host_src, staging, span_ptrs, copy_stream=None, unpack_stream=None,

@@ -8,7 +8,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <algorithm>
 #include <exception>
+#include <map>
 #include <new>
 #include <vector>
 
@@ -154,6 +156,11 @@ struct reft_plan {
     // first use at the default priority, and the events that fork it from / join it to copy_stream
     hipStream_t aux = nullptr;
     Event aux_fork, aux_join;
+    // rotated parity placement: plans derived from this one (merged piece lists of shifted
+    // windows), keyed by (kind, k, member, segment), and a small all-zero device buffer that
+    // stands in for the zero extension of the last segment
+    std::map<uint64_t, reft_plan *> derived;
+    void *zeros = nullptr;
 
     PlanTables tables() const { return PlanTables{d_off, d_first, T, L, tile_shift}; }
 };
@@ -406,6 +413,9 @@ extern "C" void reft_plan_destroy(reft_plan *p)
     drain(p->pack_begin);
     drain(p->rest_begin);
     free_ring(p);
+    for (auto &kv : p->derived) reft_plan_destroy(kv.second);
+    p->derived.clear();
+    if (p->zeros) (void)hipFree(p->zeros);
     if (p->d_off) (void)hipFree(p->d_off);
     if (p->d_first) (void)hipFree(p->d_first);
     delete p;
@@ -897,6 +907,207 @@ extern "C" int reft_parity_encode(reft_plan *p, const void *const *shard_span_pt
         done += rows;
     }
     return record(p->ring_ev[entry], s);
+}
+
+// XOR of `nrows` rows of span pointers (row stride T of plan p) into a contiguous destination or,
+// if dst_row is given, into the destination's own spans.  More than kMaxSrc rows are folded in
+// passes.  rows (and dst_row) are host arrays; they are uploaded as one table.
+static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const void *const *dst_row,
+                    void *dst_contig, hipStream_t s)
+{
+    int rc;
+    const uint64_t T = p->T;
+    const uint64_t *tab = nullptr;
+    int entry = 0;
+    if (dst_row) {
+        std::vector<const void *> all((size_t)(nrows + 1) * T);
+        std::copy(rows, rows + (size_t)nrows * T, all.begin());
+        std::copy(dst_row, dst_row + T, all.begin() + (size_t)nrows * T);
+        if ((rc = upload_ptrs(p, all.data(), nrows + 1, s, &tab, &entry))) return rc;
+    } else {
+        if ((rc = upload_ptrs(p, rows, nrows, s, &tab, &entry))) return rc;
+    }
+    const uint64_t *dtab = dst_row ? tab + (uint64_t)nrows * T : nullptr;
+    const LaunchCfg cfg = launch_cfg(p);
+    const PlanTables pt = p->tables();
+    uint32_t done = 0;
+    while (done < nrows) {
+        const bool acc = done > 0;
+        uint32_t n = nrows - done;
+        const uint32_t cap = (uint32_t)kMaxSrc - (acc ? 1u : 0u);
+        if (n > cap) n = cap;
+        HIPCHK(launch_gather(pt, tab + (uint64_t)done * T, (int)n, acc, dtab,
+                             (uint64_t)(uintptr_t)dst_contig, 0, p->L, cfg, s));
+        done += n;
+    }
+    return record(p->ring_ev[entry], s);
+}
+
+// ------------------------------------------------------------------------------------------------
+// rotated placement of the parity (section 4.2): every member protects one segment of every other
+// ------------------------------------------------------------------------------------------------
+namespace {
+// One operand of a rotated XOR: `len` bytes starting at stream offset w of a shard (bytes at or
+// beyond L read as zero), or a contiguous buffer (span_ptrs == nullptr).
+struct Window {
+    const void *const *span_ptrs;   // T span pointers of the shard, or nullptr
+    const void *contig;             // base of a contiguous operand (window offset 0)
+    uint64_t w;                     // stream offset of the window's first byte
+};
+}  // namespace
+
+static uint32_t rot_index(uint32_t i, uint32_t j) { return i < j ? i : i - 1; }
+
+extern "C" uint64_t reft_segment_bytes(const reft_plan *p, uint32_t k)
+{
+    return (!p || k < 2) ? 0 : (p->L + (k - 2)) / (k - 1);
+}
+
+// The plan whose spans are the merged pieces of windows of `len` bytes at the given stream
+// offsets of the base plan (every span boundary of every window becomes a boundary).
+static int derived_plan(reft_plan *p, uint64_t key, const std::vector<uint64_t> &offsets,
+                        uint64_t len, reft_plan **out)
+{
+    auto it = p->derived.find(key);
+    if (it != p->derived.end()) {
+        *out = it->second;
+        return REFT_OK;
+    }
+    std::vector<uint64_t> cuts{0, len};
+    for (uint64_t w : offsets) {
+        // span starts strictly inside (w, w + len)
+        auto lo = std::upper_bound(p->off.begin(), p->off.end(), w);
+        for (; lo != p->off.end() && *lo < w + len; ++lo) cuts.push_back(*lo - w);
+    }
+    std::sort(cuts.begin(), cuts.end());
+    cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
+    std::vector<uint64_t> sizes(cuts.size() - 1);
+    for (size_t i = 0; i + 1 < cuts.size(); ++i) sizes[i] = cuts[i + 1] - cuts[i];
+    reft_plan *d = nullptr;
+    int rc = reft_plan_create(sizes.data(), sizes.size(), nullptr, 0, 0, &d);
+    if (rc) return rc;
+    p->derived[key] = d;
+    *out = d;
+    return REFT_OK;
+}
+
+// Row of span pointers of derived plan d for one window.
+static int window_row(reft_plan *p, const reft_plan *d, const Window &win, const void **row)
+{
+    for (uint64_t t = 0; t < d->T; ++t) {
+        const uint64_t x = d->off[t];
+        if (!win.span_ptrs) {
+            row[t] = (const uint8_t *)win.contig + x;
+            continue;
+        }
+        const uint64_t y = win.w + x;
+        if (y >= p->L) {                       // zero extension of the last segment
+            if (d->off[t + 1] - x > 256) return fail(REFT_EINVAL, "internal: zero pad too long");
+            row[t] = p->zeros;
+            continue;
+        }
+        const uint64_t sp = (uint64_t)(std::upper_bound(p->off.begin(), p->off.end(), y) -
+                                       p->off.begin()) - 1;        // off[sp] <= y < off[sp + 1]
+        if (!win.span_ptrs[sp])
+            return fail(REFT_EINVAL, "rotated parity: span %llu is null but has bytes",
+                        (unsigned long long)sp);
+        row[t] = (const uint8_t *)win.span_ptrs[sp] + (y - p->off[sp]);
+    }
+    return REFT_OK;
+}
+
+static int ensure_zeros(reft_plan *p)
+{
+    if (p->zeros) return REFT_OK;
+    HIPCHK(hipMalloc(&p->zeros, 256));
+    HIPCHK(hipMemset(p->zeros, 0, 256));
+    return REFT_OK;
+}
+
+extern "C" int reft_parity_encode_rotated(reft_plan *p, const void *const *shard_span_ptrs,
+                                          uint32_t k, uint32_t member, void *parity_dev,
+                                          reft_stream stream)
+{
+    REFT_GUARD_BEGIN
+    int rc = check_plan(p, "reft_parity_encode_rotated");
+    if (rc) return rc;
+    if (k < 2 || k > REFT_MAX_K)
+        return fail(REFT_EINVAL, "reft_parity_encode_rotated: k = %u outside [2, %d]", k, REFT_MAX_K);
+    if (member >= k)
+        return fail(REFT_EINVAL, "reft_parity_encode_rotated: member = %u but k = %u", member, k);
+    if (!shard_span_ptrs) return fail(REFT_EINVAL, "reft_parity_encode_rotated: null pointer array");
+    const uint64_t Lseg = reft_segment_bytes(p, k);
+    if (Lseg == 0) return REFT_OK;
+    if (!parity_dev) return fail(REFT_EINVAL, "reft_parity_encode_rotated: null parity buffer");
+    if ((rc = ensure_zeros(p))) return rc;
+    std::vector<Window> wins;
+    std::vector<uint64_t> offsets;
+    for (uint32_t j = 0; j < k; ++j) {
+        if (j == member) continue;
+        wins.push_back(Window{shard_span_ptrs + (size_t)j * p->T, nullptr,
+                              (uint64_t)rot_index(member, j) * Lseg});
+        offsets.push_back(wins.back().w);
+    }
+    reft_plan *d = nullptr;
+    if ((rc = derived_plan(p, (1ull << 56) | ((uint64_t)k << 32) | member, offsets, Lseg, &d)))
+        return rc;
+    // (the end of the stream inside a window is a boundary too, because off[T] = L: the zero
+    // extension of the last segment starts on a piece boundary)
+    std::vector<const void *> rows((size_t)wins.size() * d->T);
+    for (size_t r = 0; r < wins.size(); ++r)
+        if ((rc = window_row(p, d, wins[r], rows.data() + r * d->T))) return rc;
+    return xor_rows(d, rows.data(), (uint32_t)wins.size(), nullptr, parity_dev, (hipStream_t)stream);
+    REFT_GUARD_END("reft_parity_encode_rotated")
+}
+
+extern "C" int reft_reconstruct_rotated(reft_plan *p, const void *const *shard_span_ptrs,
+                                        const void *const *parity_ptrs, uint32_t k, uint32_t lost,
+                                        void *const *out_span_ptrs, reft_stream stream)
+{
+    REFT_GUARD_BEGIN
+    int rc = check_plan(p, "reft_reconstruct_rotated");
+    if (rc) return rc;
+    if (k < 2 || k > REFT_MAX_K)
+        return fail(REFT_EINVAL, "reft_reconstruct_rotated: k = %u outside [2, %d]", k, REFT_MAX_K);
+    if (lost >= k) return fail(REFT_EINVAL, "reft_reconstruct_rotated: lost = %u but k = %u", lost, k);
+    if (!shard_span_ptrs || !parity_ptrs)
+        return fail(REFT_EINVAL, "reft_reconstruct_rotated: null pointer array");
+    if ((rc = check_span_ptrs(p, out_span_ptrs, 1, "reft_reconstruct_rotated(out)"))) return rc;
+    const uint64_t Lseg = reft_segment_bytes(p, k);
+    if (Lseg == 0) return REFT_OK;
+    if ((rc = ensure_zeros(p))) return rc;
+    for (uint32_t r = 0; r + 1 < k; ++r) {
+        const uint64_t o0 = (uint64_t)r * Lseg;
+        if (o0 >= p->L) break;
+        const uint64_t len = p->L - o0 < Lseg ? p->L - o0 : Lseg;
+        const uint32_t i = r < lost ? r : r + 1;          // the member that protects segment r
+        if (!parity_ptrs[i])
+            return fail(REFT_EINVAL, "reft_reconstruct_rotated: parity unit of member %u is null", i);
+        std::vector<Window> wins;
+        std::vector<uint64_t> offsets;
+        wins.push_back(Window{nullptr, parity_ptrs[i], 0});
+        for (uint32_t j = 0; j < k; ++j) {
+            if (j == i || j == lost) continue;
+            wins.push_back(Window{shard_span_ptrs + (size_t)j * p->T, nullptr,
+                                  (uint64_t)rot_index(i, j) * Lseg});
+            offsets.push_back(wins.back().w);
+        }
+        offsets.push_back(o0);                            // the destination's own span boundaries
+        reft_plan *d = nullptr;
+        if ((rc = derived_plan(p, (2ull << 56) | ((uint64_t)k << 32) | ((uint64_t)lost << 16) | r,
+                               offsets, len, &d)))
+            return rc;
+        std::vector<const void *> rows((size_t)wins.size() * d->T), dst(d->T);
+        for (size_t q = 0; q < wins.size(); ++q)
+            if ((rc = window_row(p, d, wins[q], rows.data() + q * d->T))) return rc;
+        const Window out_win{(const void *const *)out_span_ptrs, nullptr, o0};
+        if ((rc = window_row(p, d, out_win, dst.data()))) return rc;
+        if ((rc = xor_rows(d, rows.data(), (uint32_t)wins.size(), dst.data(), nullptr,
+                           (hipStream_t)stream)))
+            return rc;
+    }
+    return REFT_OK;
+    REFT_GUARD_END("reft_reconstruct_rotated")
 }
 
 // ------------------------------------------------------------------------------------------------
