@@ -274,6 +274,19 @@ def main() -> int:
         t_rec = timed_alone(lambda: reft.reft_reconstruct_spans(plan, p_surv, k, lost, parity2,
                                                                 p_fresh_lost, s_xor), s_xor)
         del packed
+        # the paper's rotated placement: all k members' units, then the decode of the lost member
+        Lseg = reft.reft_segment_bytes(plan, k)
+        units = [torch.empty(Lseg, dtype=torch.uint8, device=dev) for _ in range(k)]
+        p_units = reft.ptr_array(units)
+
+        def all_units():
+            for i in range(k):
+                reft.reft_parity_encode_rotated(plan, p_all, k, i, units[i], s_xor)
+        t_rot = timed_alone(all_units, s_xor)
+        t_rotdec = timed_alone(lambda: reft.reft_reconstruct_rotated(plan, p_all, p_units, k, lost,
+                                                                     p_fresh_lost, s_xor), s_xor)
+        rot_ok = all(torch.equal(a, b) for a, b in zip(fresh_lost, shards[lost]))
+        del units
 
         def snap():
             s_snap.wait_stream(s_xor)
@@ -291,12 +304,15 @@ def main() -> int:
             "unpack_kernel_GBps": round(2 * L / t_unpack / 1e9, 1),
             "parity_encode_GBps": round((k + 1) * L / t_enc / 1e9, 1),
             "reconstruct_GBps": round((k + 1) * L / t_rec / 1e9, 1),
+            "rotated_units_GBps": round(k * k * Lseg / t_rot / 1e9, 1),
+            "rotated_decode_GBps": round(k * (k - 1) * Lseg / t_rotdec / 1e9, 1),
+            "rotated_decode_verified": bool(rot_ok),
             "snapshot_d2h_GBps": round(L / t_snap / 1e9, 2),
             "restore_h2d_GBps": round(L / t_rest / 1e9, 2),
         }
         stages["pct_hbm_peak"] = {n: pct(stages[n], HBM_PEAK_GBPS) for n in
                                   ("pack_kernel_GBps", "unpack_kernel_GBps", "parity_encode_GBps",
-                                   "reconstruct_GBps")}
+                                   "reconstruct_GBps", "rotated_units_GBps", "rotated_decode_GBps")}
         stages["pct_link_peak"] = {n: pct(stages[n], LINK_PEAK_GBPS) for n in
                                    ("snapshot_d2h_GBps", "restore_h2d_GBps")}
 
