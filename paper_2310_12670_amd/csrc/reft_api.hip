@@ -148,7 +148,10 @@ struct reft_plan {
     uint64_t *h_ptr = nullptr;
     uint64_t *d_ptr = nullptr;
     Event ring_ev[kRing];
-    unsigned ring_next = 0;
+    uint32_t ring_len[kRing] = {};    // pointers held by entry e (0 = empty)
+    uint64_t ring_used[kRing] = {};   // tick of the entry's last use (least recently used goes first)
+    uint32_t ring_hits[kRing] = {};   // reuses since the entry was uploaded
+    uint64_t ring_tick = 0;
     // bucket pipelines
     Event pack_filled[kGroups], pack_free[kGroups], pack_done, pack_begin, rest_begin;
     Event rest_filled[kGroups], rest_free[kGroups], rest_done, rest_copied;
@@ -230,6 +233,7 @@ static int ensure_ring(reft_plan *p, uint32_t rows)
     for (int i = 0; i < kRing; ++i)
         if (p->ring_ev[i].recorded) HIPCHK(hipEventSynchronize(p->ring_ev[i].ev));
     free_ring(p);
+    for (int i = 0; i < kRing; ++i) p->ring_len[i] = 0;
     const size_t bytes = (size_t)kRing * rows * p->T * sizeof(uint64_t);
     HIPCHK(hipHostMalloc((void **)&p->h_ptr, bytes, hipHostMallocDefault));
     HIPCHK(hipMalloc((void **)&p->d_ptr, bytes));
@@ -237,21 +241,42 @@ static int ensure_ring(reft_plan *p, uint32_t rows)
     return REFT_OK;
 }
 
-// Copy `rows` x T pointers into the next ring entry and start its upload on `s`.
-// On success *dev_tab is the device table and *entry the ring index to release after the last
-// kernel that reads it.
+// Make `rows` x T pointers available on the device: reuse the ring entry that already holds exactly
+// these pointers (a trainer passes the same tensors every iteration), else overwrite the least
+// recently used entry and start its upload on `s`.  On success *dev_tab is the device table and
+// *entry the ring index, whose event the caller records after the last kernel that reads it.
 static int upload_ptrs(reft_plan *p, const void *const *ptrs, uint32_t rows, hipStream_t s,
                        const uint64_t **dev_tab, int *entry)
 {
     int rc = ensure_ring(p, rows < 8 ? 8 : rows);
     if (rc) return rc;
-    const int e = (int)(p->ring_next++ % kRing);
-    if (p->ring_ev[e].recorded) HIPCHK(hipEventSynchronize(p->ring_ev[e].ev));
     const size_t stride = (size_t)p->ring_rows * p->T;
     const size_t n = (size_t)rows * p->T;
-    uint64_t *h = p->h_ptr + e * stride;
-    for (size_t i = 0; i < n; ++i) h[i] = (uint64_t)(uintptr_t)ptrs[i];
-    HIPCHK(hipMemcpyAsync(p->d_ptr + e * stride, h, n * sizeof(uint64_t), hipMemcpyHostToDevice, s));
+    static_assert(sizeof(void *) == sizeof(uint64_t), "pointers are 64-bit");
+    int e = -1;
+    for (int i = 0; i < kRing && e < 0; ++i)
+        if (p->ring_len[i] == n && !memcmp(p->h_ptr + i * stride, ptrs, n * sizeof(uint64_t))) e = i;
+    if (e < 0) {
+        e = 0;
+        for (int i = 1; i < kRing; ++i)
+            if (p->ring_used[i] < p->ring_used[e]) e = i;
+        // Nothing may still be reading the entry.  Its event covers the most recent use only, so
+        // an entry that was shared by several calls (possibly on different streams) is freed the
+        // safe way: wait for the whole device.  This is off the steady-state path (cache hits).
+        if (p->ring_hits[e]) HIPCHK(hipDeviceSynchronize());
+        else if (p->ring_ev[e].recorded) HIPCHK(hipEventSynchronize(p->ring_ev[e].ev));
+        uint64_t *h = p->h_ptr + e * stride;
+        memcpy(h, ptrs, n * sizeof(uint64_t));
+        p->ring_len[e] = (uint32_t)n;
+        p->ring_hits[e] = 0;
+        HIPCHK(hipMemcpyAsync(p->d_ptr + e * stride, h, n * sizeof(uint64_t), hipMemcpyHostToDevice,
+                              s));
+    } else {
+        // the table was uploaded on some stream earlier: this stream must see the upload
+        if (p->ring_ev[e].recorded) HIPCHK(hipStreamWaitEvent(s, p->ring_ev[e].ev, 0));
+        p->ring_hits[e] += 1;
+    }
+    p->ring_used[e] = ++p->ring_tick;
     *dev_tab = p->d_ptr + e * stride;
     *entry = e;
     return REFT_OK;
