@@ -904,36 +904,6 @@ extern "C" int reft_unpack_device(reft_plan *p, const void *src_dev, uint64_t sr
 // ------------------------------------------------------------------------------------------------
 // S4: parity over span tables
 // ------------------------------------------------------------------------------------------------
-extern "C" int reft_parity_encode(reft_plan *p, const void *const *shard_span_ptrs, uint32_t k,
-                                  void *parity_dev, reft_stream stream)
-{
-    int rc = check_plan(p, "reft_parity_encode");
-    if (rc) return rc;
-    if (k < 1 || k > REFT_MAX_K)
-        return fail(REFT_EINVAL, "reft_parity_encode: k = %u outside [1, %d]", k, REFT_MAX_K);
-    if ((rc = check_span_ptrs(p, shard_span_ptrs, k, "reft_parity_encode"))) return rc;
-    if (p->L == 0) return REFT_OK;
-    if (!parity_dev) return fail(REFT_EINVAL, "reft_parity_encode: null parity buffer");
-    hipStream_t s = (hipStream_t)stream;
-    const uint64_t *tab = nullptr;
-    int entry = 0;
-    if ((rc = upload_ptrs(p, shard_span_ptrs, k, s, &tab, &entry))) return rc;
-    const LaunchCfg cfg = launch_cfg(p);
-    const PlanTables pt = p->tables();
-    // up to kMaxSrc shards per pass; later passes fold further shards into the parity
-    uint32_t done = 0;
-    while (done < k) {
-        const bool acc = done > 0;
-        uint32_t rows = k - done;
-        const uint32_t cap = (uint32_t)kMaxSrc - (acc ? 1u : 0u);
-        if (rows > cap) rows = cap;
-        HIPCHK(launch_gather(pt, tab + (uint64_t)done * p->T, (int)rows, acc, nullptr,
-                             (uint64_t)(uintptr_t)parity_dev, 0, p->L, cfg, s));
-        done += rows;
-    }
-    return record(p->ring_ev[entry], s);
-}
-
 // XOR of `nrows` rows of span pointers (row stride T of plan p) into a contiguous destination or,
 // if dst_row is given, into the destination's own spans.  More than kMaxSrc rows are folded in
 // passes.  rows (and dst_row) are host arrays; they are uploaded as one table.
@@ -966,6 +936,21 @@ static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const
         done += n;
     }
     return record(p->ring_ev[entry], s);
+}
+
+extern "C" int reft_parity_encode(reft_plan *p, const void *const *shard_span_ptrs, uint32_t k,
+                                  void *parity_dev, reft_stream stream)
+{
+    REFT_GUARD_BEGIN
+    int rc = check_plan(p, "reft_parity_encode");
+    if (rc) return rc;
+    if (k < 1 || k > REFT_MAX_K)
+        return fail(REFT_EINVAL, "reft_parity_encode: k = %u outside [1, %d]", k, REFT_MAX_K);
+    if ((rc = check_span_ptrs(p, shard_span_ptrs, k, "reft_parity_encode"))) return rc;
+    if (p->L == 0) return REFT_OK;
+    if (!parity_dev) return fail(REFT_EINVAL, "reft_parity_encode: null parity buffer");
+    return xor_rows(p, shard_span_ptrs, k, nullptr, parity_dev, (hipStream_t)stream);
+    REFT_GUARD_END("reft_parity_encode")
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1195,9 +1180,9 @@ extern "C" int reft_reconstruct_spans(reft_plan *p, const void *const *shard_spa
     if (lost >= k) return fail(REFT_EINVAL, "reft_reconstruct_spans: lost = %u but k = %u", lost, k);
     if (!shard_span_ptrs) return fail(REFT_EINVAL, "reft_reconstruct_spans: null pointer array");
     if ((rc = check_span_ptrs(p, out_span_ptrs, 1, "reft_reconstruct_spans(out)"))) return rc;
-    // rows: the k-1 survivors, then the parity expressed as a span row, then the destination
+    // rows: the k-1 survivors, then the parity expressed as a span row
     const uint64_t T = p->T;
-    std::vector<const void *> rows((size_t)(k + 1) * T);
+    std::vector<const void *> rows((size_t)k * T);
     uint32_t r = 0;
     for (uint32_t s = 0; s < k; ++s) {
         if (s == lost) continue;
@@ -1211,24 +1196,8 @@ extern "C" int reft_reconstruct_spans(reft_plan *p, const void *const *shard_spa
     for (uint64_t t = 0; t < T; ++t)
         rows[(size_t)r * T + t] = (const uint8_t *)parity_dev + p->off[t];
     ++r;                                                       // r == k source rows
-    for (uint64_t t = 0; t < T; ++t) rows[(size_t)r * T + t] = out_span_ptrs[t];
-    hipStream_t s = (hipStream_t)stream;
-    const uint64_t *tab = nullptr;
-    int entry = 0;
-    if ((rc = upload_ptrs(p, rows.data(), k + 1, s, &tab, &entry))) return rc;
-    const uint64_t *dtab = tab + (uint64_t)k * T;
-    const LaunchCfg cfg = launch_cfg(p);
-    const PlanTables pt = p->tables();
-    uint32_t done = 0;
-    while (done < k) {
-        const bool acc = done > 0;
-        uint32_t n = k - done;
-        const uint32_t cap = (uint32_t)kMaxSrc - (acc ? 1u : 0u);
-        if (n > cap) n = cap;
-        HIPCHK(launch_gather(pt, tab + (uint64_t)done * T, (int)n, acc, dtab, 0, 0, p->L, cfg, s));
-        done += n;
-    }
-    return record(p->ring_ev[entry], s);
+    return xor_rows(p, rows.data(), k, (const void *const *)out_span_ptrs, nullptr,
+                    (hipStream_t)stream);
     REFT_GUARD_END("reft_reconstruct_spans")
 }
 
