@@ -57,6 +57,13 @@ static std::atomic<uint64_t> g_small_pieces{8}; // spans starting in a tile that
 static std::atomic<uint64_t> g_dma_min{65536};   // pieces of at least this many bytes are copied by DMA
 static std::atomic<uint64_t> g_gather_min{8};    // shortest run of smaller pieces worth a gather kernel
 static std::atomic<uint64_t> g_dma_streams{1};   // 2 = piece copies alternate with a helper stream
+static std::atomic<uint64_t> g_burst{1};         // parity encode may use the write-burst kernel
+static std::atomic<uint64_t> g_burst_min_rows{4};    // ... from this many sources on
+static std::atomic<uint64_t> g_burst_min_bytes{8ull << 20};  // ... and from this stream length on
+static std::atomic<uint64_t> g_burst_stage{32768};   // stream bytes per workgroup and round
+static std::atomic<uint64_t> g_burst_wgs{2};         // resident workgroups per compute unit
+static std::atomic<uint64_t> g_burst_polls{64};      // bound on a writer wave's wait (0 = no waiting)
+static std::atomic<uint64_t> g_burst_nap{16};        // pause between polls, units of 1024 cycles
 
 extern "C" int reft_set_tunable(const char *name, uint64_t value)
 {
@@ -91,6 +98,28 @@ extern "C" int reft_set_tunable(const char *name, uint64_t value)
     } else if (!strcmp(name, "host_only_plans")) {
         if (value > 1) return fail(REFT_EINVAL, "host_only_plans must be 0 or 1");
         g_host_only = value;
+    } else if (!strcmp(name, "burst")) {
+        if (value > 1) return fail(REFT_EINVAL, "burst must be 0 or 1");
+        g_burst = value;
+    } else if (!strcmp(name, "burst_min_rows")) {
+        if (value < 1) return fail(REFT_EINVAL, "burst_min_rows must be at least 1");
+        g_burst_min_rows = value;
+    } else if (!strcmp(name, "burst_min_bytes")) {
+        g_burst_min_bytes = value;
+    } else if (!strcmp(name, "burst_stage_bytes")) {
+        if (value < 4096 || value > 65536 || value % 4096)
+            return fail(REFT_EINVAL, "burst_stage_bytes must be a multiple of 4096 in [4096, 65536]");
+        g_burst_stage = value;
+    } else if (!strcmp(name, "burst_wgs_per_cu")) {
+        if (value < 1 || value > 8) return fail(REFT_EINVAL, "burst_wgs_per_cu must be in [1, 8]");
+        g_burst_wgs = value;
+    } else if (!strcmp(name, "burst_max_polls")) {
+        if (value > 100000) return fail(REFT_EINVAL, "burst_max_polls must be at most 100000");
+        g_burst_polls = value;
+    } else if (!strcmp(name, "burst_nap")) {
+        if (value > 1024) return fail(REFT_EINVAL, "burst_nap must be at most 1024");
+        g_burst_nap = value;
+
     } else {
         return fail(REFT_EINVAL, "unknown tunable '%s'", name);
     }
@@ -110,6 +139,13 @@ extern "C" int reft_get_tunable(const char *name, uint64_t *value)
     else if (!strcmp(name, "dma_min_bytes")) *value = g_dma_min;
     else if (!strcmp(name, "gather_min_pieces")) *value = g_gather_min;
     else if (!strcmp(name, "dma_streams")) *value = g_dma_streams;
+    else if (!strcmp(name, "burst")) *value = g_burst;
+    else if (!strcmp(name, "burst_min_rows")) *value = g_burst_min_rows;
+    else if (!strcmp(name, "burst_min_bytes")) *value = g_burst_min_bytes;
+    else if (!strcmp(name, "burst_stage_bytes")) *value = g_burst_stage;
+    else if (!strcmp(name, "burst_wgs_per_cu")) *value = g_burst_wgs;
+    else if (!strcmp(name, "burst_max_polls")) *value = g_burst_polls;
+    else if (!strcmp(name, "burst_nap")) *value = g_burst_nap;
     else return fail(REFT_EINVAL, "unknown tunable '%s'", name);
     return REFT_OK;
 }
@@ -164,6 +200,11 @@ struct reft_plan {
     // stands in for the zero extension of the last segment
     std::map<uint64_t, reft_plan *> derived;
     void *zeros = nullptr;
+    // write-burst kernel: most spans that start in one tile (dense tiles keep the ordinary kernel)
+    // and a ring of counter blocks, one per launch in flight, allocated on first use
+    uint32_t max_tile_spans = 0;
+    uint32_t *burst_ctr = nullptr;
+    uint32_t burst_next = 0;
 
     PlanTables tables() const { return PlanTables{d_off, d_first, T, L, tile_shift}; }
 };
@@ -373,6 +414,10 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
             while (p->off[i + 1] <= o) ++i;      // o < L = off[T] keeps i < T
             first[t] = (uint32_t)i;
         }
+        for (uint64_t t = 0; t < p->ntiles; ++t) {
+            const uint64_t nxt = t + 1 < p->ntiles ? first[t + 1] : T - 1;
+            if (nxt - first[t] > p->max_tile_spans) p->max_tile_spans = (uint32_t)(nxt - first[t]);
+        }
     }
 
     if (g_host_only.load()) {
@@ -438,6 +483,7 @@ extern "C" void reft_plan_destroy(reft_plan *p)
     drain(p->pack_begin);
     drain(p->rest_begin);
     free_ring(p);
+    if (p->burst_ctr) (void)hipFree(p->burst_ctr);
     for (auto &kv : p->derived) reft_plan_destroy(kv.second);
     p->derived.clear();
     if (p->zeros) (void)hipFree(p->zeros);
@@ -925,6 +971,39 @@ static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const
     const uint64_t *dtab = dst_row ? tab + (uint64_t)nrows * T : nullptr;
     const LaunchCfg cfg = launch_cfg(p);
     const PlanTables pt = p->tables();
+    // One pass over many rows: reads and writes are separated in time by the burst kernel (plans
+    // with tiles dense in small spans keep the ordinary kernel, whose LDS-staged path serves those
+    // better; so do ragged destinations whose spans are not all aligned alike relative to their
+    // stream offsets, which the burst kernel's staging image cannot represent).
+    if (nrows <= (uint32_t)kMaxSrc && g_burst.load() && nrows >= g_burst_min_rows.load() &&
+        p->L >= g_burst_min_bytes.load() && p->max_tile_spans < cfg.small_pieces) {
+        uint64_t vb = (uint64_t)(uintptr_t)dst_contig;
+        bool alike = true;
+        if (dst_row) {
+            bool have = false;
+            for (uint64_t t = 0; t < T && alike; ++t) {
+                if (p->off[t + 1] == p->off[t]) continue;
+                const uint64_t c = ((uint64_t)(uintptr_t)dst_row[t] - p->off[t]) & 15u;
+                if (!have) { vb = c; have = true; }
+                else alike = c == vb;
+            }
+        }
+        if (alike) {
+            constexpr uint32_t kCtrBlocks = 8;
+            if (!p->burst_ctr)
+                HIPCHK(hipMalloc((void **)&p->burst_ctr, kCtrBlocks * kBurstCtrBytes));
+            BurstCfg bc;
+            bc.ctr = p->burst_ctr +
+                     (size_t)(p->burst_next++ % kCtrBlocks) * (kBurstCtrBytes / sizeof(uint32_t));
+            bc.stage_bytes = (uint32_t)g_burst_stage.load();
+            bc.wgs_per_cu = (uint32_t)g_burst_wgs.load();
+            bc.num_cus = (uint32_t)p->num_cus;
+            bc.max_polls = (uint32_t)g_burst_polls.load();
+            bc.nap = (uint32_t)g_burst_nap.load();
+            HIPCHK(launch_gather_burst(pt, tab, (int)nrows, dtab, vb, 0, p->L, cfg, bc, s));
+            return record(p->ring_ev[entry], s);
+        }
+    }
     uint32_t done = 0;
     while (done < nrows) {
         const bool acc = done > 0;

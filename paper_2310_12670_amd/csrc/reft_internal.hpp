@@ -26,6 +26,17 @@ struct PlanTables {
     uint32_t tile_shift;           // tile = 1 << tile_shift stream bytes
 };
 
+// Parameters of the gather variant that writes in chip-wide bursts (see k_gather_burst).
+struct BurstCfg {
+    uint32_t *ctr;                 // 9 * 64 words of device memory for this launch alone
+    uint32_t stage_bytes;          // stream bytes a workgroup buffers in LDS per round (x2 halves)
+    uint32_t wgs_per_cu;           // cap on resident workgroups per compute unit
+    uint32_t num_cus;
+    uint32_t max_polls;            // bound on a writer wave's wait for the others (0 = never wait)
+    uint32_t nap;                  // pause between polls, in units of 1024 cycles
+};
+constexpr size_t kBurstCtrBytes = 9 * 64 * sizeof(uint32_t);
+
 // Sources passed by value for the contiguous XOR kernel.
 struct SrcBases {
     uint64_t p[kMaxSrc];
@@ -38,6 +49,14 @@ struct SrcBases {
 hipError_t launch_gather(const PlanTables &pt, const uint64_t *tab, int nrows, bool acc,
                          const uint64_t *dtab, uint64_t dst_vbase, uint64_t lo, uint64_t hi,
                          const LaunchCfg &cfg, hipStream_t stream);
+
+// The same result as launch_gather with acc = false, by the burst kernel.  With dtab == null the
+// destination is contiguous and vb its virtual base.  With dtab, every span with bytes must
+// satisfy (dtab[i] - off[i]) mod 16 == vb mod 16 (the caller checks; otherwise use launch_gather).
+// stage_bytes: a multiple of 4096, at most 65536.
+hipError_t launch_gather_burst(const PlanTables &pt, const uint64_t *tab, int nrows,
+                               const uint64_t *dtab, uint64_t vb, uint64_t lo, uint64_t hi,
+                               const LaunchCfg &cfg, const BurstCfg &bc, hipStream_t stream);
 
 // src_vbase + o is the source address of stream byte o; tab is one row of T span pointers.
 hipError_t launch_scatter(const PlanTables &pt, const uint64_t *tab, uint64_t src_vbase,

@@ -15,6 +15,10 @@
 //   contig  dst[i] = XOR_s src_s[i]
 #include "reft_internal.hpp"
 
+#include <map>
+#include <mutex>
+#include <utility>
+
 namespace reft {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -80,14 +84,35 @@ __device__ __forceinline__ u32x4 load_any(uint64_t addr, uint32_t c)
     return shift_bytes(lo, hi, r);
 }
 
+// Where the bytes of a piece go: to their global address, or into an LDS image of a destination
+// range (image byte 0 stands for the 16-byte aligned address `origin`), from which another wave
+// stores them later.
+#define REFT_LDS __attribute__((address_space(3)))
+struct ToGlobal {
+    template <bool NT>
+    __device__ __forceinline__ void put16(uint64_t a, u32x4 v) const { st16<NT>(as_g16(a), v); }
+    __device__ __forceinline__ void put8(uint64_t a, uint8_t v) const { st8(a, v); }
+};
+struct ToImage {
+    REFT_LDS unsigned char *img;
+    uint64_t origin;
+    template <bool NT>
+    __device__ __forceinline__ void put16(uint64_t a, u32x4 v) const
+    {
+        *(REFT_LDS u32x4 *)(img + (uint32_t)(a - origin)) = v;
+    }
+    __device__ __forceinline__ void put8(uint64_t a, uint8_t v) const { img[(uint32_t)(a - origin)] = v; }
+};
+
 // One piece: n bytes at destination address d = XOR of the n bytes at each source address s[j].
 // The whole workgroup cooperates.  Destination stores are 16-byte aligned: up to 15 head bytes
 // and 15 tail bytes are moved bytewise, the body as 16-byte chunks.  If every source is
 // co-aligned with the destination (the case for tensors whose sizes and addresses are multiples
 // of 16) the body is plain vector loads, U chunks in flight per thread and source; otherwise each
 // misaligned source is read as two aligned chunks and byte-shifted in registers.
-template <int K, int U, bool NT>
-__device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], uint32_t n)
+template <int K, int U, bool NT, class Sink = ToGlobal>
+__device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], uint32_t n,
+                                          const Sink sink = Sink())
 {
     const uint32_t tid = threadIdx.x;
     uint32_t head = (uint32_t)(0 - d) & 15u;
@@ -104,12 +129,12 @@ __device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], ui
             uint8_t v = ld8(s[0] + i);
 #pragma unroll
             for (int j = 1; j < K; ++j) v ^= ld8(s[j] + i);
-            st8(d + i, v);
+            sink.put8(d + i, v);
         }
     }
     if (nb == 0) return;
 
-    gptr16 dp = as_g16(d + head);
+    const uint64_t da = d + head;
     uint32_t mis = 0;
 #pragma unroll
     for (int j = 0; j < K; ++j) mis |= (uint32_t)(s[j] + head) & 15u;
@@ -130,20 +155,21 @@ __device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], ui
                 for (int u = 0; u < U; ++u) v[u] ^= ld16<NT>(sp[j] + c + u * kThreads);
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) st16<NT>(dp + c + u * kThreads, v[u]);
+            for (int u = 0; u < U; ++u)
+                sink.template put16<NT>(da + ((uint64_t)(c + u * kThreads) << 4), v[u]);
         }
         for (uint32_t c = full + tid; c < nb; c += kThreads) {
             u32x4 v = ld16<NT>(sp[0] + c);
 #pragma unroll
             for (int j = 1; j < K; ++j) v ^= ld16<NT>(sp[j] + c);
-            st16<NT>(dp + c, v);
+            sink.template put16<NT>(da + ((uint64_t)c << 4), v);
         }
     } else {
         for (uint32_t c = tid; c < nb; c += kThreads) {
             u32x4 v = load_any<NT>(s[0] + head, c);
 #pragma unroll
             for (int j = 1; j < K; ++j) v ^= load_any<NT>(s[j] + head, c);
-            st16<NT>(dp + c, v);
+            sink.template put16<NT>(da + ((uint64_t)c << 4), v);
         }
     }
 }
@@ -376,6 +402,152 @@ k_gather(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *__rest
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Gather with write bursts (many sources, one pass).
+//
+// Measured on this part: a stream of reads runs at about 7 TB/s, but as soon as writes are mixed
+// into it, even a few, the whole stream drops to 5.2 - 5.9 TB/s; the same bytes written in short
+// chip-wide bursts cost far less.  So this variant separates the two in time.  A workgroup has
+// four reader waves and one writer wave.  The readers XOR one stage (stage_bytes of the stream)
+// after another into the two halves of an LDS double buffer and never touch the destination.
+// The writer wave stores stage r-1 from its half while the readers fill the other half with stage
+// r - but not before every workgroup of the grid has finished reading its stage r-1, so that
+// all writer waves of the chip fire together.  That meeting is only a matter of timing: it is a
+// counter the writer wave polls a bounded number of times (readers never wait for another
+// workgroup), a workgroup that once polls in vain stops waiting for good, and the result does not
+// depend on it.  The grid is persistent (launch_gather_burst sizes it so that all workgroups are
+// resident); workgroup b takes stages b, b + grid, ...
+//
+// The LDS image of a stage is laid out like the destination: the byte of stream offset o sits
+// where address vb + o would fall relative to a 16-byte boundary.  For a contiguous destination
+// vb is its virtual base.  For a ragged one (dtab), every span's place must have the same
+// alignment relative to its stream offset, (dtab[i] - off[i]) mod 16 = vb mod 16 for all spans
+// with bytes (the host checks this); then aligned 16-byte chunks of the image are aligned
+// 16-byte chunks of every destination span.
+//
+// ctr: 9 counters kCtrStride words apart, all zero at launch.  Workgroups arrive on counter
+// (blockIdx.x & 7); the last arrival of a group for a round bumps counter 8, the only one polled.
+// ------------------------------------------------------------------------------------------------
+constexpr int kBurstThreads = kThreads + 64;
+constexpr uint32_t kCtrStride = 64;
+
+// One wave moves len bytes from an LDS image to global address d (img is the byte for d; img and d
+// have the same alignment mod 16).
+template <bool NT>
+__device__ __forceinline__ void emit_piece(uint64_t d, REFT_LDS const unsigned char *img,
+                                           uint32_t len, uint32_t lane)
+{
+    uint32_t head = (uint32_t)(0 - d) & 15u;
+    if (head > len) head = len;
+    const uint32_t nb = (len - head) >> 4;
+    const uint32_t tail = (len - head) & 15u;
+    if (lane < head) {
+        st8(d + lane, img[lane]);
+    } else if (lane >= 16 && lane - 16 < tail) {
+        const uint32_t b = head + (nb << 4) + (lane - 16);
+        st8(d + b, img[b]);
+    }
+    if (nb) {
+        gptr16 dp = as_g16(d + head);
+        REFT_LDS const u32x4 *ip = (REFT_LDS const u32x4 *)(img + head);
+#pragma unroll 8
+        for (uint32_t c = lane; c < nb; c += 64) st16<NT>(dp + c, ip[c]);
+    }
+}
+
+template <int K, int U, bool NT>
+__global__ void __launch_bounds__(kBurstThreads)
+k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *__restrict__ dtab,
+               uint64_t vb, uint64_t lo, uint64_t hi, uint32_t stage, uint32_t *ctr,
+               uint32_t max_polls, uint32_t nap)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char burst_lds[];
+    REFT_LDS unsigned char *lds = (REFT_LDS unsigned char *)burst_lds;
+    const uint32_t half = stage + 16;                  // an image may start up to 15 bytes in
+    const uint32_t lane = threadIdx.x & 63;
+    const bool writer = threadIdx.x >= kThreads;
+    const uint32_t G = gridDim.x, g = blockIdx.x & 7;
+    const uint64_t nstages = (hi - lo + stage - 1) / stage;
+    const uint64_t rounds = (nstages + G - 1) / G;
+    const uint32_t members = (G - g + 7) >> 3;         // workgroups that arrive on counter g
+    const uint32_t ngroups = G < 8 ? G : 8;
+    bool timed = max_polls != 0;
+
+    for (uint64_t r = 0; r <= rounds; ++r) {
+        if (!writer) {
+            const uint64_t st = r * G + blockIdx.x;
+            if (r < rounds && st < nstages) {
+                uint64_t o = lo + st * stage;
+                uint64_t e = o + stage;
+                if (e > hi) e = hi;
+                const ToImage sink{lds + (uint32_t)(r & 1) * half, (vb + o) & ~15ull};
+                uint32_t i = pt.first_span[o >> pt.tile_shift];
+                while (o < e) {
+                    // o < e <= L = off[T], so a span with off[i+1] > o exists at or after i
+                    while (pt.off[i + 1] <= o) ++i;
+                    const uint64_t so = pt.off[i];
+                    uint64_t pe = pt.off[i + 1];
+                    if (pe > e) pe = e;
+                    uint64_t s[K];
+#pragma unroll
+                    for (int j = 0; j < K; ++j) s[j] = tab[(uint64_t)j * pt.T + i] + (o - so);
+                    xor_piece<K, U, NT, ToImage>(vb + o, s, (uint32_t)(pe - o), sink);
+                    o = pe;
+                }
+            }
+        } else if (r > 0) {
+            if (timed) {
+                const uint32_t want = ngroups * (uint32_t)r;   // every group done with round r-1
+                for (uint32_t n = 0;;) {
+                    uint32_t v = 0;
+                    if (lane == 0)
+                        v = __hip_atomic_load(ctr + 8 * kCtrStride, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
+                    v = __builtin_amdgcn_readfirstlane(v);
+                    if (v >= want) break;
+                    if (++n >= max_polls) { timed = false; break; }
+                    for (uint32_t z = 0; z < nap; ++z) __builtin_amdgcn_s_sleep(16);
+                }
+            }
+            const uint64_t st = (r - 1) * G + blockIdx.x;
+            if (st < nstages) {
+                uint64_t o = lo + st * stage;
+                const uint64_t e = o + stage < hi ? o + stage : hi;
+                // image byte of stream offset x: img0[x - o]
+                REFT_LDS const unsigned char *img0 =
+                    lds + (uint32_t)((r - 1) & 1) * half + ((uint32_t)(vb + o) & 15u);
+                if (dtab == nullptr) {
+                    emit_piece<NT>(vb + o, img0, (uint32_t)(e - o), lane);
+                } else {
+                    const uint64_t o0 = o;
+                    uint32_t i = pt.first_span[o >> pt.tile_shift];
+                    while (o < e) {
+                        while (pt.off[i + 1] <= o) ++i;
+                        const uint64_t so = pt.off[i];
+                        const uint64_t pe = pt.off[i + 1] < e ? pt.off[i + 1] : e;
+                        emit_piece<NT>(dtab[i] + (o - so), img0 + (uint32_t)(o - o0),
+                                       (uint32_t)(pe - o), lane);
+                        o = pe;
+                    }
+                }
+            }
+        }
+        __syncthreads();       // stage r is complete in LDS; stage r-1 has left its half
+        if (writer && lane == 0 && r < rounds) {
+            const uint32_t old = __hip_atomic_fetch_add(ctr + g * kCtrStride, 1u, __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT);
+            if (old + 1 == ((uint32_t)r + 1) * members)
+                __hip_atomic_fetch_add(ctr + 8 * kCtrStride, 1u, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+__global__ void k_zero_words(uint32_t *p, uint32_t n)
+{
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
+}
+
 // tab[span(o)] + offset of o in its span  <-  src_vbase + o
 template <int U, bool NT>
 __global__ void __launch_bounds__(kThreads)
@@ -469,6 +641,53 @@ hipError_t launch_gather(const PlanTables &pt, const uint64_t *tab, int nrows, b
     const uint64_t ntiles = ((hi - 1) >> pt.tile_shift) - (lo >> pt.tile_shift) + 1;
     hipLaunchKernelGGL(fn, dim3(grid_for(ntiles, cfg)), dim3(kThreads), 0, stream, pt, tab, dtab,
                        dst_vbase, lo, hi, acc ? 1u : 0u, cfg.small_pieces);
+    return hipGetLastError();
+}
+
+// Workgroups of the burst kernel that fit on one compute unit with `lds` bytes of LDS each
+// (looked up once per instantiation; the first call also lifts the kernel's LDS limit).
+static hipError_t burst_occupancy(const void *fn, size_t lds, int *per_cu)
+{
+    static std::mutex mu;
+    static std::map<std::pair<const void *, size_t>, int> known;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = known.find({fn, lds});
+    if (it == known.end()) {
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        int n = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, kBurstThreads, lds);
+        if (e != hipSuccess) return e;
+        it = known.emplace(std::make_pair(fn, lds), n).first;
+    }
+    *per_cu = it->second;
+    return hipSuccess;
+}
+
+hipError_t launch_gather_burst(const PlanTables &pt, const uint64_t *tab, int nrows,
+                               const uint64_t *dtab, uint64_t vb, uint64_t lo, uint64_t hi,
+                               const LaunchCfg &cfg, const BurstCfg &bc, hipStream_t stream)
+{
+    if (lo >= hi) return hipSuccess;
+    if (hi > pt.L || !bc.ctr || bc.stage_bytes < 4096 || bc.stage_bytes % 4096 ||
+        bc.stage_bytes > 65536 || bc.wgs_per_cu < 1 || bc.num_cus < 1)
+        return hipErrorInvalidValue;
+    void (*fn)(PlanTables, const uint64_t *, const uint64_t *, uint64_t, uint64_t, uint64_t, uint32_t,
+               uint32_t *, uint32_t, uint32_t) = nullptr;
+    REFT_PICK_K(k_gather_burst, fn, nrows)
+    const size_t lds = 2 * ((size_t)bc.stage_bytes + 16);
+    int per_cu = 0;
+    hipError_t e = burst_occupancy((const void *)fn, lds, &per_cu);
+    if (e != hipSuccess) return e;
+    if (per_cu < 1) return hipErrorInvalidValue;
+    if ((uint32_t)per_cu > bc.wgs_per_cu) per_cu = (int)bc.wgs_per_cu;
+    const uint64_t nstages = (hi - lo + bc.stage_bytes - 1) / bc.stage_bytes;
+    uint64_t grid = (uint64_t)per_cu * bc.num_cus;     // all resident at once
+    if (grid > cfg.max_wgs) grid = cfg.max_wgs;
+    if (grid > nstages) grid = nstages;
+    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(256), 0, stream, bc.ctr, 9 * kCtrStride);
+    hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kBurstThreads), lds, stream, pt, tab,
+                       dtab, vb, lo, hi, bc.stage_bytes, bc.ctr, bc.max_polls, bc.nap);
     return hipGetLastError();
 }
 
