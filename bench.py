@@ -80,6 +80,15 @@ def main() -> int:
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device-to-device copy of 1 GiB (torch), the kernel of "
                          "known size that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--overlap-encode", action="store_true",
+                    help="start the own shard's snapshot first and run the parity encode beside it")
+    ap.add_argument("--no-burst", action="store_true",
+                    help="XOR kernels without write bursts (the ordinary gather kernel), for comparison")
+    ap.add_argument("--burst-polls", type=int, default=-1,
+                    help="tunable burst_max_polls (0 = write bursts are not timed)")
+    ap.add_argument("--burst-nap", type=int, default=-1, help="tunable burst_nap")
+    ap.add_argument("--burst-stage", type=int, default=0, help="tunable burst_stage_bytes")
+    ap.add_argument("--burst-wgs", type=int, default=0, help="tunable burst_wgs_per_cu")
     ap.add_argument("--no-stages", action="store_true", help="skip the per-stage measurements")
     ap.add_argument("--has-demo", action="store_true",
                     help="instead of the benchmark: run a synthetic pipeline-stage timeline (idle "
@@ -155,6 +164,16 @@ def main() -> int:
         reft.reft_set_tunable("link_wgs", args.link_wgs)
     if args.dma_streams:
         reft.reft_set_tunable("dma_streams", args.dma_streams)
+    if args.no_burst:
+        reft.reft_set_tunable("burst", 0)
+    if args.burst_polls >= 0:
+        reft.reft_set_tunable("burst_max_polls", args.burst_polls)
+    if args.burst_nap >= 0:
+        reft.reft_set_tunable("burst_nap", args.burst_nap)
+    if args.burst_stage:
+        reft.reft_set_tunable("burst_stage_bytes", args.burst_stage)
+    if args.burst_wgs:
+        reft.reft_set_tunable("burst_wgs_per_cu", args.burst_wgs)
     # s_snap / s_load carry the link-bound work (and, staged, the gather / scatter kernels);
     # s_copy / s_h2d carry the DMA transfers of the staged path; s_xor the HBM-bound XOR kernels.
     s_snap, s_xor, s_load = (torch.cuda.Stream() for _ in range(3))
@@ -162,13 +181,25 @@ def main() -> int:
     s_h2d = torch.cuda.Stream() if load_staged and args.two_stream_load else s_load
     snap_done_stream = s_copy
     enc_events, rec_events = [], []
+    # The runtime maps streams to its few hardware queues in the order in which they first get
+    # work; two streams on one queue run in turn.  Touch them in an order that keeps the two copy
+    # directions and the XOR kernels apart.
+    for st in (s_snap, s_copy, s_xor, s_load, s_h2d):
+        with torch.cuda.stream(st):
+            torch.zeros(1, device=dev)
+    torch.cuda.synchronize()
 
     def save_phase(timed):
-        """Snapshot of the own shard beside the parity encode, then the parity's snapshot.
-        Returns the event after which the own shard's host copy is complete."""
-        reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_snap, s_copy)
-        own_done = torch.cuda.Event()
-        own_done.record(snap_done_stream)
+        """Parity encode, then the snapshot of the own shard, then the parity's snapshot.
+        Returns the event after which the own shard's host copy is complete.  The encode runs
+        before the copies start (16 ms during which the link idles): beside copy traffic that
+        the runtime executes as kernels, as it does under rocprofv3, the write-burst kernel is
+        several times slower, and a trainer would place the encode in a bubble anyway.
+        --overlap-encode starts the own shard's snapshot first and the encode beside it."""
+        if args.overlap_encode:
+            reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_snap, s_copy)
+            own_done = torch.cuda.Event()
+            own_done.record(snap_done_stream)
         if timed:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(s_xor)
@@ -177,6 +208,10 @@ def main() -> int:
             e1.record(s_xor)
             enc_events.append((e0, e1))
         s_snap.wait_stream(s_xor)
+        if not args.overlap_encode:
+            reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_snap, s_copy)
+            own_done = torch.cuda.Event()
+            own_done.record(snap_done_stream)
         reft.reft_snapshot_pack(pplan, p_par, stag_psave, host_par, s_snap, s_copy)
         return own_done
 
@@ -413,8 +448,9 @@ def main() -> int:
         "config": {
             "workload": f"config {wl.cfg}: {wl.description}",
             "k": k, "spans": T, "stream_bytes": L, "buckets": len(wl.bucket_nbytes),
-            "step": "snapshot own shard + XOR parity + snapshot parity to pinned host, then "
+            "step": "XOR parity, snapshot own shard + parity to pinned host, then "
                     "restore shard + parity from host and reconstruct the lost shard",
+            "encode_beside_copies": bool(args.overlap_encode),
             "value_bytes_per_step": 4 * L,
             "save_path": args.save_path, "load_path": args.load_path,
             "staging_mib": args.staging_mib,
@@ -425,8 +461,9 @@ def main() -> int:
         },
         "verified": bool(verified),
         "roofline": {
-            "kernel": "k_gather<8> (parity encode over 8 span tables)" if k == 8 else
-                      f"k_gather<{k}> (parity encode)",
+            "kernel": f"k_gather_burst<{k}> (parity encode over {k} span tables)"
+                      if reft.reft_get_tunable("burst") and k >= reft.reft_get_tunable("burst_min_rows")
+                      else f"k_gather<{k}> (parity encode over {k} span tables)",
             "bound": "hbm",
             "achieved": round(enc_gbps, 1),
             "peak": HBM_PEAK_GBPS,
@@ -542,7 +579,7 @@ def measured_traffic(cfg: int):
     """HBM bytes per launch of the encode kernel from the committed rocprofv3 counter runs
     (FETCH_SIZE and WRITE_SIZE, each scaled by a copy of known size), or None if no such profile
     exists for this configuration."""
-    path = os.path.join(ROOT, "profiles", f"config{cfg}_k_gather8_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"config{cfg}_k_gather_burst8_hbm_traffic.txt")
     try:
         kv = {}
         for line in open(path):

@@ -287,6 +287,20 @@ int reft_restore_wait(reft_plan *plan);
  *   "small_pieces" a tile in which at least this many spans start is processed by the LDS-staged
  *                  small-piece path of the gather / scatter kernels (default 8; 4294967295 = never,
  *                  0 = always).
+ *   "burst"        1 (default) = reft_parity_encode, reft_reconstruct_spans and the rotated calls use
+ *                  the write-burst variant of the XOR kernel where it applies: one pass (at most 8
+ *                  rows), at least "burst_min_rows" rows (default 4) and "burst_min_bytes" stream
+ *                  bytes (default 8 MiB), no tile dense in small spans (see "small_pieces"), and, for
+ *                  a decode into tensors, every tensor's address aligned alike (mod 16) relative to
+ *                  its stream offset.  The variant keeps reads and writes apart in time: reader
+ *                  waves XOR "burst_stage_bytes" (default 32768; a multiple of 4096, at most 65536)
+ *                  of the stream at a time into LDS, and one writer wave per workgroup stores the
+ *                  previous stage once all workgroups of the (persistent, "burst_wgs_per_cu" per
+ *                  compute unit, default 2) grid have read theirs.  The writer waits by polling a
+ *                  counter at most "burst_max_polls" times per round (default 6; 0 = never waits),
+ *                  "burst_nap" x 1024 cycles apart (default 16); a writer whose wait runs out
+ *                  does not wait at all for the next 1, 2, 4, ... 64 rounds.  Timing only: results
+ *                  never depend on it.  0 = always the ordinary kernel.
  * Read when a plan is created:
  *   "tile_shift"   log2 of the tile size in bytes, 12..24 (default 18 = 256 KiB).
  *   "host_only_plans"  1 = reft_plan_create builds only the host-side sizing (no GPU needed);

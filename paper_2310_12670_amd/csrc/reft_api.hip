@@ -62,7 +62,7 @@ static std::atomic<uint64_t> g_burst_min_rows{4};    // ... from this many sourc
 static std::atomic<uint64_t> g_burst_min_bytes{8ull << 20};  // ... and from this stream length on
 static std::atomic<uint64_t> g_burst_stage{32768};   // stream bytes per workgroup and round
 static std::atomic<uint64_t> g_burst_wgs{2};         // resident workgroups per compute unit
-static std::atomic<uint64_t> g_burst_polls{64};      // bound on a writer wave's wait (0 = no waiting)
+static std::atomic<uint64_t> g_burst_polls{6};       // bound on a writer wave's wait per round (0 = no waiting)
 static std::atomic<uint64_t> g_burst_nap{16};        // pause between polls, units of 1024 cycles
 
 extern "C" int reft_set_tunable(const char *name, uint64_t value)

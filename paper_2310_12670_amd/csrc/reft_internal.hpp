@@ -32,7 +32,7 @@ struct BurstCfg {
     uint32_t stage_bytes;          // stream bytes a workgroup buffers in LDS per round (x2 halves)
     uint32_t wgs_per_cu;           // cap on resident workgroups per compute unit
     uint32_t num_cus;
-    uint32_t max_polls;            // bound on a writer wave's wait for the others (0 = never wait)
+    uint32_t max_polls;            // bound on a writer wave's wait per round (0 = never wait)
     uint32_t nap;                  // pause between polls, in units of 1024 cycles
 };
 constexpr size_t kBurstCtrBytes = 9 * 64 * sizeof(uint32_t);

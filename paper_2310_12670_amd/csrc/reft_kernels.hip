@@ -413,9 +413,10 @@ k_gather(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *__rest
 // The writer wave stores stage r-1 from its half while the readers fill the other half with stage
 // r - but not before every workgroup of the grid has finished reading its stage r-1, so that
 // all writer waves of the chip fire together.  That meeting is only a matter of timing: it is a
-// counter the writer wave polls a bounded number of times (readers never wait for another
-// workgroup), a workgroup that once polls in vain stops waiting for good, and the result does not
-// depend on it.  The grid is persistent (launch_gather_burst sizes it so that all workgroups are
+// counter the writer wave polls at most max_polls times per round (readers never wait for another
+// workgroup), a writer that polls in vain stops waiting for the next 1, 2, 4, ... 64 rounds (so a
+// slow workgroup, or one that is not resident, costs the others next to nothing), and the result
+// does not depend on it.  The grid is persistent (launch_gather_burst sizes it so that all workgroups are
 // resident); workgroup b takes stages b, b + grid, ...
 //
 // The LDS image of a stage is laid out like the destination: the byte of stream offset o sits
@@ -471,7 +472,7 @@ k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *
     const uint64_t rounds = (nstages + G - 1) / G;
     const uint32_t members = (G - g + 7) >> 3;         // workgroups that arrive on counter g
     const uint32_t ngroups = G < 8 ? G : 8;
-    bool timed = max_polls != 0;
+    uint32_t skip = 0, backoff = 0;                    // writer wave: rounds left without waiting
 
     for (uint64_t r = 0; r <= rounds; ++r) {
         if (!writer) {
@@ -496,7 +497,9 @@ k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *
                 }
             }
         } else if (r > 0) {
-            if (timed) {
+            if (skip) {
+                --skip;
+            } else if (max_polls) {
                 const uint32_t want = ngroups * (uint32_t)r;   // every group done with round r-1
                 for (uint32_t n = 0;;) {
                     uint32_t v = 0;
@@ -504,8 +507,13 @@ k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *
                         v = __hip_atomic_load(ctr + 8 * kCtrStride, __ATOMIC_RELAXED,
                                               __HIP_MEMORY_SCOPE_AGENT);
                     v = __builtin_amdgcn_readfirstlane(v);
-                    if (v >= want) break;
-                    if (++n >= max_polls) { timed = false; break; }
+                    if (v >= want) { backoff = 0; break; }
+                    if (++n >= max_polls) {
+                        // a straggler: write without the others for 1, 2, 4, ... 64 rounds
+                        backoff = backoff == 0 ? 1 : backoff < 64 ? backoff * 2 : 64;
+                        skip = backoff;
+                        break;
+                    }
                     for (uint32_t z = 0; z < nap; ++z) __builtin_amdgcn_s_sleep(16);
                 }
             }
@@ -533,7 +541,7 @@ k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *
             }
         }
         __syncthreads();       // stage r is complete in LDS; stage r-1 has left its half
-        if (writer && lane == 0 && r < rounds) {
+        if (writer && lane == 0 && r < rounds && max_polls) {
             const uint32_t old = __hip_atomic_fetch_add(ctr + g * kCtrStride, 1u, __ATOMIC_RELAXED,
                                                         __HIP_MEMORY_SCOPE_AGENT);
             if (old + 1 == ((uint32_t)r + 1) * members)
