@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <exception>
 #include <map>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -950,6 +951,26 @@ extern "C" int reft_unpack_device(reft_plan *p, const void *src_dev, uint64_t sr
 // ------------------------------------------------------------------------------------------------
 // S4: parity over span tables
 // ------------------------------------------------------------------------------------------------
+constexpr uint32_t kCtrBlocks = 8;      // burst launches that may be in flight on one ring
+
+static BurstCfg burst_cfg(uint32_t *ring, uint32_t slot, int num_cus)
+{
+    BurstCfg bc;
+    bc.ctr = ring + (size_t)(slot % kCtrBlocks) * (kBurstCtrBytes / sizeof(uint32_t));
+    bc.stage_bytes = (uint32_t)g_burst_stage.load();
+    bc.wgs_per_cu = (uint32_t)g_burst_wgs.load();
+    bc.num_cus = (uint32_t)num_cus;
+    bc.max_polls = (uint32_t)g_burst_polls.load();
+    bc.nap = (uint32_t)g_burst_nap.load();
+    return bc;
+}
+
+static bool burst_wanted(uint32_t nrows, uint64_t L)
+{
+    return nrows <= (uint32_t)kMaxSrc && g_burst.load() && nrows >= g_burst_min_rows.load() &&
+           L >= g_burst_min_bytes.load();
+}
+
 // XOR of `nrows` rows of span pointers (row stride T of plan p) into a contiguous destination or,
 // if dst_row is given, into the destination's own spans.  More than kMaxSrc rows are folded in
 // passes.  rows (and dst_row) are host arrays; they are uploaded as one table.
@@ -975,8 +996,7 @@ static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const
     // with tiles dense in small spans keep the ordinary kernel, whose LDS-staged path serves those
     // better; so do ragged destinations whose spans are not all aligned alike relative to their
     // stream offsets, which the burst kernel's staging image cannot represent).
-    if (nrows <= (uint32_t)kMaxSrc && g_burst.load() && nrows >= g_burst_min_rows.load() &&
-        p->L >= g_burst_min_bytes.load() && p->max_tile_spans < cfg.small_pieces) {
+    if (burst_wanted(nrows, p->L) && p->max_tile_spans < cfg.small_pieces) {
         uint64_t vb = (uint64_t)(uintptr_t)dst_contig;
         bool alike = true;
         if (dst_row) {
@@ -989,17 +1009,9 @@ static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const
             }
         }
         if (alike) {
-            constexpr uint32_t kCtrBlocks = 8;
             if (!p->burst_ctr)
                 HIPCHK(hipMalloc((void **)&p->burst_ctr, kCtrBlocks * kBurstCtrBytes));
-            BurstCfg bc;
-            bc.ctr = p->burst_ctr +
-                     (size_t)(p->burst_next++ % kCtrBlocks) * (kBurstCtrBytes / sizeof(uint32_t));
-            bc.stage_bytes = (uint32_t)g_burst_stage.load();
-            bc.wgs_per_cu = (uint32_t)g_burst_wgs.load();
-            bc.num_cus = (uint32_t)p->num_cus;
-            bc.max_polls = (uint32_t)g_burst_polls.load();
-            bc.nap = (uint32_t)g_burst_nap.load();
+            const BurstCfg bc = burst_cfg(p->burst_ctr, p->burst_next++, p->num_cus);
             HIPCHK(launch_gather_burst(pt, tab, (int)nrows, dtab, vb, 0, p->L, cfg, bc, s));
             return record(p->ring_ev[entry], s);
         }
@@ -1206,6 +1218,7 @@ extern "C" int reft_reconstruct(const void *const *shards, uint32_t k, const voi
                                 uint64_t L, void *out_dev, uint32_t *lost_index,
                                 reft_stream stream)
 {
+    REFT_GUARD_BEGIN
     if (!shards) return fail(REFT_EINVAL, "reft_reconstruct: null shard array");
     if (k < 1 || k > REFT_MAX_K - 1)
         return fail(REFT_EINVAL, "reft_reconstruct: k = %u outside [1, %d]", k, REFT_MAX_K - 1);
@@ -1233,6 +1246,33 @@ extern "C" int reft_reconstruct(const void *const *shards, uint32_t k, const voi
     const LaunchCfg cfg = launch_cfg(nullptr);
     const uint32_t tile_shift = (uint32_t)g_tile_shift.load();
     hipStream_t st = (hipStream_t)stream;
+    if (burst_wanted(n, L)) {
+        // one pass: reads and writes separated in time (counter blocks from a ring per device,
+        // allocated on first use and kept until the process ends)
+        static std::mutex mu;
+        static std::map<int, std::pair<uint32_t *, int>> rings;   // device -> (ring, compute units)
+        static uint32_t next_slot = 0;
+        int dev = 0;
+        HIPCHK(hipGetDevice(&dev));
+        BurstCfg bc;
+        {
+            std::lock_guard<std::mutex> lock(mu);
+            auto it = rings.find(dev);
+            if (it == rings.end()) {
+                uint32_t *ring = nullptr;
+                hipDeviceProp_t prop;
+                HIPCHK(hipGetDeviceProperties(&prop, dev));
+                HIPCHK(hipMalloc((void **)&ring, kCtrBlocks * kBurstCtrBytes));
+                it = rings.emplace(dev, std::make_pair(ring, prop.multiProcessorCount > 0
+                                                                 ? prop.multiProcessorCount : 256)).first;
+            }
+            bc = burst_cfg(it->second.first, next_slot++, it->second.second);
+        }
+        SrcBases b{};
+        for (uint32_t j = 0; j < n; ++j) b.p[j] = src[j];
+        HIPCHK(launch_xor_contig_burst(b, (int)n, (uint64_t)(uintptr_t)out_dev, L, cfg, bc, st));
+        return REFT_OK;
+    }
     uint32_t done = 0;
     while (done < n) {
         SrcBases b{};
@@ -1242,6 +1282,7 @@ extern "C" int reft_reconstruct(const void *const *shards, uint32_t k, const voi
         HIPCHK(launch_xor_contig(b, m, (uint64_t)(uintptr_t)out_dev, L, tile_shift, cfg, st));
     }
     return REFT_OK;
+    REFT_GUARD_END("reft_reconstruct")
 }
 
 // S6 + S7 in one pass: survivors read in place through their span tables, the parity as a

@@ -62,8 +62,11 @@ hipError_t launch_gather_burst(const PlanTables &pt, const uint64_t *tab, int nr
 hipError_t launch_scatter(const PlanTables &pt, const uint64_t *tab, uint64_t src_vbase,
                           uint64_t lo, uint64_t hi, const LaunchCfg &cfg, hipStream_t stream);
 
-// dst[i] = XOR over s < nsrc of src.p[s][i], i in [0, L); any alignment.
+// dst[i] = XOR over s < nsrc of src.p[s][i], i in [0, L); any alignment.  The _burst form gives the
+// same bytes with reads and writes separated in time (see k_gather_burst).
 hipError_t launch_xor_contig(const SrcBases &src, int nsrc, uint64_t dst, uint64_t L,
                              uint32_t tile_shift, const LaunchCfg &cfg, hipStream_t stream);
+hipError_t launch_xor_contig_burst(const SrcBases &src, int nsrc, uint64_t dst, uint64_t L,
+                                   const LaunchCfg &cfg, const BurstCfg &bc, hipStream_t stream);
 
 }  // namespace reft

@@ -456,11 +456,11 @@ __device__ __forceinline__ void emit_piece(uint64_t d, REFT_LDS const unsigned c
     }
 }
 
-template <int K, int U, bool NT>
-__global__ void __launch_bounds__(kBurstThreads)
-k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *__restrict__ dtab,
-               uint64_t vb, uint64_t lo, uint64_t hi, uint32_t stage, uint32_t *ctr,
-               uint32_t max_polls, uint32_t nap)
+// The rounds of a burst kernel.  read(st, img) is run by the 256 reader threads and puts stage st
+// into the LDS image at img; emit(st, img, lane) is run by the writer wave and stores the image.
+template <class Read, class Emit>
+__device__ __forceinline__ void burst_rounds(uint64_t nstages, uint32_t stage, uint32_t *ctr,
+                                             uint32_t max_polls, uint32_t nap, Read read, Emit emit)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char burst_lds[];
     REFT_LDS unsigned char *lds = (REFT_LDS unsigned char *)burst_lds;
@@ -468,7 +468,6 @@ k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *
     const uint32_t lane = threadIdx.x & 63;
     const bool writer = threadIdx.x >= kThreads;
     const uint32_t G = gridDim.x, g = blockIdx.x & 7;
-    const uint64_t nstages = (hi - lo + stage - 1) / stage;
     const uint64_t rounds = (nstages + G - 1) / G;
     const uint32_t members = (G - g + 7) >> 3;         // workgroups that arrive on counter g
     const uint32_t ngroups = G < 8 ? G : 8;
@@ -477,25 +476,7 @@ k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *
     for (uint64_t r = 0; r <= rounds; ++r) {
         if (!writer) {
             const uint64_t st = r * G + blockIdx.x;
-            if (r < rounds && st < nstages) {
-                uint64_t o = lo + st * stage;
-                uint64_t e = o + stage;
-                if (e > hi) e = hi;
-                const ToImage sink{lds + (uint32_t)(r & 1) * half, (vb + o) & ~15ull};
-                uint32_t i = pt.first_span[o >> pt.tile_shift];
-                while (o < e) {
-                    // o < e <= L = off[T], so a span with off[i+1] > o exists at or after i
-                    while (pt.off[i + 1] <= o) ++i;
-                    const uint64_t so = pt.off[i];
-                    uint64_t pe = pt.off[i + 1];
-                    if (pe > e) pe = e;
-                    uint64_t s[K];
-#pragma unroll
-                    for (int j = 0; j < K; ++j) s[j] = tab[(uint64_t)j * pt.T + i] + (o - so);
-                    xor_piece<K, U, NT, ToImage>(vb + o, s, (uint32_t)(pe - o), sink);
-                    o = pe;
-                }
-            }
+            if (r < rounds && st < nstages) read(st, lds + (uint32_t)(r & 1) * half);
         } else if (r > 0) {
             if (skip) {
                 --skip;
@@ -518,27 +499,7 @@ k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *
                 }
             }
             const uint64_t st = (r - 1) * G + blockIdx.x;
-            if (st < nstages) {
-                uint64_t o = lo + st * stage;
-                const uint64_t e = o + stage < hi ? o + stage : hi;
-                // image byte of stream offset x: img0[x - o]
-                REFT_LDS const unsigned char *img0 =
-                    lds + (uint32_t)((r - 1) & 1) * half + ((uint32_t)(vb + o) & 15u);
-                if (dtab == nullptr) {
-                    emit_piece<NT>(vb + o, img0, (uint32_t)(e - o), lane);
-                } else {
-                    const uint64_t o0 = o;
-                    uint32_t i = pt.first_span[o >> pt.tile_shift];
-                    while (o < e) {
-                        while (pt.off[i + 1] <= o) ++i;
-                        const uint64_t so = pt.off[i];
-                        const uint64_t pe = pt.off[i + 1] < e ? pt.off[i + 1] : e;
-                        emit_piece<NT>(dtab[i] + (o - so), img0 + (uint32_t)(o - o0),
-                                       (uint32_t)(pe - o), lane);
-                        o = pe;
-                    }
-                }
-            }
+            if (st < nstages) emit(st, lds + (uint32_t)((r - 1) & 1) * half, lane);
         }
         __syncthreads();       // stage r is complete in LDS; stage r-1 has left its half
         if (writer && lane == 0 && r < rounds && max_polls) {
@@ -549,6 +510,80 @@ k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *
                                        __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+}
+
+template <int K, int U, bool NT>
+__global__ void __launch_bounds__(kBurstThreads)
+k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *__restrict__ dtab,
+               uint64_t vb, uint64_t lo, uint64_t hi, uint32_t stage, uint32_t *ctr,
+               uint32_t max_polls, uint32_t nap)
+{
+    const uint64_t nstages = (hi - lo + stage - 1) / stage;
+    burst_rounds(
+        nstages, stage, ctr, max_polls, nap,
+        [&](uint64_t st, REFT_LDS unsigned char *img) {
+            uint64_t o = lo + st * stage;
+            uint64_t e = o + stage;
+            if (e > hi) e = hi;
+            const ToImage sink{img, (vb + o) & ~15ull};
+            uint32_t i = pt.first_span[o >> pt.tile_shift];
+            while (o < e) {
+                // o < e <= L = off[T], so a span with off[i+1] > o exists at or after i
+                while (pt.off[i + 1] <= o) ++i;
+                const uint64_t so = pt.off[i];
+                uint64_t pe = pt.off[i + 1];
+                if (pe > e) pe = e;
+                uint64_t s[K];
+#pragma unroll
+                for (int j = 0; j < K; ++j) s[j] = tab[(uint64_t)j * pt.T + i] + (o - so);
+                xor_piece<K, U, NT, ToImage>(vb + o, s, (uint32_t)(pe - o), sink);
+                o = pe;
+            }
+        },
+        [&](uint64_t st, REFT_LDS const unsigned char *img, uint32_t lane) {
+            uint64_t o = lo + st * stage;
+            const uint64_t e = o + stage < hi ? o + stage : hi;
+            // image byte of stream offset x: img0[x - o]
+            REFT_LDS const unsigned char *img0 = img + ((uint32_t)(vb + o) & 15u);
+            if (dtab == nullptr) {
+                emit_piece<NT>(vb + o, img0, (uint32_t)(e - o), lane);
+            } else {
+                const uint64_t o0 = o;
+                uint32_t i = pt.first_span[o >> pt.tile_shift];
+                while (o < e) {
+                    while (pt.off[i + 1] <= o) ++i;
+                    const uint64_t so = pt.off[i];
+                    const uint64_t pe = pt.off[i + 1] < e ? pt.off[i + 1] : e;
+                    emit_piece<NT>(dtab[i] + (o - so), img0 + (uint32_t)(o - o0), (uint32_t)(pe - o),
+                                   lane);
+                    o = pe;
+                }
+            }
+        });
+}
+
+// dst[i] = XOR_j src.p[j][i], i in [0, L), with write bursts
+template <int K, int U, bool NT>
+__global__ void __launch_bounds__(kBurstThreads)
+k_xor_contig_burst(SrcBases src, uint64_t dst, uint64_t L, uint32_t stage, uint32_t *ctr,
+                   uint32_t max_polls, uint32_t nap)
+{
+    const uint64_t nstages = (L + stage - 1) / stage;
+    burst_rounds(
+        nstages, stage, ctr, max_polls, nap,
+        [&](uint64_t st, REFT_LDS unsigned char *img) {
+            const uint64_t o = st * stage;
+            const uint64_t n = L - o < stage ? L - o : stage;
+            uint64_t s[K];
+#pragma unroll
+            for (int j = 0; j < K; ++j) s[j] = src.p[j] + o;
+            xor_piece<K, U, NT, ToImage>(dst + o, s, (uint32_t)n, ToImage{img, (dst + o) & ~15ull});
+        },
+        [&](uint64_t st, REFT_LDS const unsigned char *img, uint32_t lane) {
+            const uint64_t o = st * stage;
+            const uint64_t n = L - o < stage ? L - o : stage;
+            emit_piece<NT>(dst + o, img + ((uint32_t)(dst + o) & 15u), (uint32_t)n, lane);
+        });
 }
 
 __global__ void k_zero_words(uint32_t *p, uint32_t n)
@@ -672,30 +707,64 @@ static hipError_t burst_occupancy(const void *fn, size_t lds, int *per_cu)
     return hipSuccess;
 }
 
+static bool burst_cfg_ok(const BurstCfg &bc)
+{
+    return bc.ctr && bc.stage_bytes >= 4096 && bc.stage_bytes % 4096 == 0 &&
+           bc.stage_bytes <= 65536 && bc.wgs_per_cu >= 1 && bc.num_cus >= 1;
+}
+
+// Grid of a burst launch: every workgroup resident at once.
+static hipError_t burst_grid(const void *fn, uint64_t nstages, const LaunchCfg &cfg,
+                             const BurstCfg &bc, size_t *lds, uint32_t *grid)
+{
+    *lds = 2 * ((size_t)bc.stage_bytes + 16);
+    int per_cu = 0;
+    hipError_t e = burst_occupancy(fn, *lds, &per_cu);
+    if (e != hipSuccess) return e;
+    if (per_cu < 1) return hipErrorInvalidValue;
+    if ((uint32_t)per_cu > bc.wgs_per_cu) per_cu = (int)bc.wgs_per_cu;
+    uint64_t g = (uint64_t)per_cu * bc.num_cus;
+    if (g > cfg.max_wgs) g = cfg.max_wgs;
+    if (g > nstages) g = nstages;
+    *grid = (uint32_t)g;
+    return hipSuccess;
+}
+
 hipError_t launch_gather_burst(const PlanTables &pt, const uint64_t *tab, int nrows,
                                const uint64_t *dtab, uint64_t vb, uint64_t lo, uint64_t hi,
                                const LaunchCfg &cfg, const BurstCfg &bc, hipStream_t stream)
 {
     if (lo >= hi) return hipSuccess;
-    if (hi > pt.L || !bc.ctr || bc.stage_bytes < 4096 || bc.stage_bytes % 4096 ||
-        bc.stage_bytes > 65536 || bc.wgs_per_cu < 1 || bc.num_cus < 1)
-        return hipErrorInvalidValue;
+    if (hi > pt.L || !burst_cfg_ok(bc)) return hipErrorInvalidValue;
     void (*fn)(PlanTables, const uint64_t *, const uint64_t *, uint64_t, uint64_t, uint64_t, uint32_t,
                uint32_t *, uint32_t, uint32_t) = nullptr;
     REFT_PICK_K(k_gather_burst, fn, nrows)
-    const size_t lds = 2 * ((size_t)bc.stage_bytes + 16);
-    int per_cu = 0;
-    hipError_t e = burst_occupancy((const void *)fn, lds, &per_cu);
-    if (e != hipSuccess) return e;
-    if (per_cu < 1) return hipErrorInvalidValue;
-    if ((uint32_t)per_cu > bc.wgs_per_cu) per_cu = (int)bc.wgs_per_cu;
+    size_t lds = 0;
+    uint32_t grid = 0;
     const uint64_t nstages = (hi - lo + bc.stage_bytes - 1) / bc.stage_bytes;
-    uint64_t grid = (uint64_t)per_cu * bc.num_cus;     // all resident at once
-    if (grid > cfg.max_wgs) grid = cfg.max_wgs;
-    if (grid > nstages) grid = nstages;
+    hipError_t e = burst_grid((const void *)fn, nstages, cfg, bc, &lds, &grid);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(256), 0, stream, bc.ctr, 9 * kCtrStride);
-    hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kBurstThreads), lds, stream, pt, tab,
-                       dtab, vb, lo, hi, bc.stage_bytes, bc.ctr, bc.max_polls, bc.nap);
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(kBurstThreads), lds, stream, pt, tab, dtab, vb, lo, hi,
+                       bc.stage_bytes, bc.ctr, bc.max_polls, bc.nap);
+    return hipGetLastError();
+}
+
+hipError_t launch_xor_contig_burst(const SrcBases &src, int nsrc, uint64_t dst, uint64_t L,
+                                   const LaunchCfg &cfg, const BurstCfg &bc, hipStream_t stream)
+{
+    if (L == 0) return hipSuccess;
+    if (!burst_cfg_ok(bc)) return hipErrorInvalidValue;
+    void (*fn)(SrcBases, uint64_t, uint64_t, uint32_t, uint32_t *, uint32_t, uint32_t) = nullptr;
+    REFT_PICK_K(k_xor_contig_burst, fn, nsrc)
+    size_t lds = 0;
+    uint32_t grid = 0;
+    const uint64_t nstages = (L + bc.stage_bytes - 1) / bc.stage_bytes;
+    hipError_t e = burst_grid((const void *)fn, nstages, cfg, bc, &lds, &grid);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(256), 0, stream, bc.ctr, 9 * kCtrStride);
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(kBurstThreads), lds, stream, src, dst, L,
+                       bc.stage_bytes, bc.ctr, bc.max_polls, bc.nap);
     return hipGetLastError();
 }
 

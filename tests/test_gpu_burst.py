@@ -215,3 +215,30 @@ def test_same_result_as_the_ordinary_kernel_and_back_to_back(dev):
     check_decode(dev, shards, sizes, ref, wl.lost, [0] * len(sizes))
     streams = [oracle.pack([oracle.as_bytes(t.cpu()) for t in sh]) for sh in shards]
     assert np.array_equal(ref.cpu().numpy(), oracle.encode(streams))
+
+
+@pytest.mark.parametrize("L", [1, 15, 16, 17, 4096, 32767, 32768, 32769, 100003, (1 << 20) + 5, 3 * (1 << 20)])
+@pytest.mark.parametrize("k,phase", [(1, 0), (3, 0), (4, 5), (7, 11)])
+def test_decode_from_packed_streams(dev, L, k, phase):
+    """reft_reconstruct (contiguous survivors, parity and output) through the burst variant of the
+    contiguous XOR kernel: every source count of one pass, odd addresses, ragged last stage."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(L * 31 + k)
+    raws = [torch.randint(0, 256, (L + 64,), dtype=torch.uint8, device=dev, generator=gen) for _ in range(k)]
+    streams = [r[(phase * (s + 1)) % 16:][:L] for s, r in enumerate(raws)]
+    cpu = [s.cpu().numpy() for s in streams]
+    par_np = oracle.encode(cpu)
+    praw = torch.full((L + 64,), CANARY, dtype=torch.uint8, device=dev)
+    par = praw[(phase * 3) % 16:][:L]
+    par.copy_(torch.from_numpy(par_np))
+    lost = (L + k) % k
+    want = oracle.reconstruct([c for s, c in enumerate(cpu) if s != lost], par_np)
+    assert np.array_equal(want, cpu[lost])
+    raw = torch.full((L + 2 * GUARD + phase,), CANARY, dtype=torch.uint8, device=dev)
+    out = raw[GUARD + phase:GUARD + phase + L]
+    got_lost = reft.reft_reconstruct([None if s == lost else t for s, t in enumerate(streams)], par, L, out)
+    torch.cuda.synchronize()
+    assert got_lost == lost
+    r = raw.cpu().numpy()
+    assert np.array_equal(r[GUARD + phase:GUARD + phase + L], want)
+    assert np.all(r[:GUARD + phase] == CANARY) and np.all(r[GUARD + phase + L:] == CANARY)
