@@ -161,15 +161,27 @@ def test_reconstruct_argument_checks_need_no_gpu():
 
 def test_tunables():
     for name, good, bad in (("unroll", 2, 3), ("nontemporal", 0, 2), ("tile_shift", 14, 40),
-                            ("max_wgs", 64, 1 << 30)):
+                            ("max_wgs", 64, 1 << 30), ("link_wgs", 8, 0), ("dma_streams", 2, 3),
+                            ("gather_min_pieces", 3, 0), ("small_pieces", 5, 1 << 40),
+                            ("burst", 0, 2), ("burst_min_rows", 2, 0),
+                            ("burst_stage_bytes", 16384, 5000), ("burst_stage_bytes", 65536, 131072),
+                            ("burst_wgs_per_cu", 3, 9), ("burst_max_polls", 0, 1 << 20),
+                            ("burst_nap", 4, 4096)):
         old = reft.reft_get_tunable(name)
         reft.reft_set_tunable(name, good)
         assert reft.reft_get_tunable(name) == good
         with pytest.raises(reft.ReftError):
             reft.reft_set_tunable(name, bad)
         reft.reft_set_tunable(name, old)
+    for name in ("dma_min_bytes", "burst_min_bytes"):        # any value is valid
+        old = reft.reft_get_tunable(name)
+        reft.reft_set_tunable(name, 12345)
+        assert reft.reft_get_tunable(name) == 12345
+        reft.reft_set_tunable(name, old)
     with pytest.raises(reft.ReftError):
         reft.reft_set_tunable("no_such_knob", 1)
+    with pytest.raises(reft.ReftError):
+        reft.reft_get_tunable("no_such_knob")
 
 
 def test_plans_of_the_five_configurations(host_only):
