@@ -196,6 +196,9 @@ int reft_parity_encode(reft_plan *plan, const void *const *shard_span_ptrs, uint
 /* ---- S6: decode the single lost shard (section 4.2, Eq. 2) ---------------------------------------
  * out_dev[i] = parity[i] ^ (XOR over the surviving shards s of shards[s][i]), i in [0, L).
  *
+ * (The first call on a device allocates 18 KiB of device memory for the XOR kernel's counters
+ * and keeps it until the process ends.)
+ *
  * shards[k]   host array of device pointers to the packed streams (L bytes each) of the node's k
  *             shards; exactly one entry is NULL: the lost shard.
  * parity      device pointer, L bytes.   out_dev: device buffer of L bytes, no overlap with inputs.

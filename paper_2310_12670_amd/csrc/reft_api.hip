@@ -161,6 +161,7 @@ namespace {
 constexpr int kRing = 16;       // pointer-table uploads that may be in flight at once
 constexpr int kMaxSlots = 64;   // staging slots used by the staged bucket pipelines
 constexpr int kGroups = 2;      // the slots form two groups that alternate (double buffering)
+constexpr uint32_t kCtrBlocks = 8;  // burst launches that may be in flight on one ring of counters
 
 struct Event {
     hipEvent_t ev = nullptr;
@@ -202,7 +203,7 @@ struct reft_plan {
     std::map<uint64_t, reft_plan *> derived;
     void *zeros = nullptr;
     // write-burst kernel: most spans that start in one tile (dense tiles keep the ordinary kernel)
-    // and a ring of counter blocks, one per launch in flight, allocated on first use
+    // and a ring of counter blocks, one per launch in flight
     uint32_t max_tile_spans = 0;
     uint32_t *burst_ctr = nullptr;
     uint32_t burst_next = 0;
@@ -436,6 +437,7 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
     HIPCHK(hipMemcpy(p->d_off, p->off.data(), (T + 1) * sizeof(uint64_t), hipMemcpyHostToDevice));
     HIPCHK(hipMemcpy(p->d_first, first.data(), first.size() * sizeof(uint32_t),
                      hipMemcpyHostToDevice));
+    HIPCHK(hipMalloc((void **)&p->burst_ctr, kCtrBlocks * kBurstCtrBytes));
     int rc;
     for (int i = 0; i < kRing; ++i)
         if ((rc = make_event(p->ring_ev[i]))) return rc;
@@ -951,8 +953,6 @@ extern "C" int reft_unpack_device(reft_plan *p, const void *src_dev, uint64_t sr
 // ------------------------------------------------------------------------------------------------
 // S4: parity over span tables
 // ------------------------------------------------------------------------------------------------
-constexpr uint32_t kCtrBlocks = 8;      // burst launches that may be in flight on one ring
-
 static BurstCfg burst_cfg(uint32_t *ring, uint32_t slot, int num_cus)
 {
     BurstCfg bc;
@@ -1009,8 +1009,6 @@ static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const
             }
         }
         if (alike) {
-            if (!p->burst_ctr)
-                HIPCHK(hipMalloc((void **)&p->burst_ctr, kCtrBlocks * kBurstCtrBytes));
             const BurstCfg bc = burst_cfg(p->burst_ctr, p->burst_next++, p->num_cus);
             HIPCHK(launch_gather_burst(pt, tab, (int)nrows, dtab, vb, 0, p->L, cfg, bc, s));
             return record(p->ring_ev[entry], s);

@@ -416,8 +416,8 @@ k_gather(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *__rest
 // counter the writer wave polls at most max_polls times per round (readers never wait for another
 // workgroup), a writer that polls in vain stops waiting for the next 1, 2, 4, ... 64 rounds (so a
 // slow workgroup, or one that is not resident, costs the others next to nothing), and the result
-// does not depend on it.  The grid is persistent (launch_gather_burst sizes it so that all workgroups are
-// resident); workgroup b takes stages b, b + grid, ...
+// does not depend on it.  The grid is persistent (the launch wrappers size it so that all
+// workgroups are resident); workgroup b takes stages b, b + grid, ...
 //
 // The LDS image of a stage is laid out like the destination: the byte of stream offset o sits
 // where address vb + o would fall relative to a 16-byte boundary.  For a contiguous destination
