@@ -293,9 +293,10 @@ int reft_restore_wait(reft_plan *plan);
  *   "burst"        1 (default) = reft_parity_encode, reft_reconstruct_spans and the rotated calls use
  *                  the write-burst variant of the XOR kernel where it applies: one pass (at most 8
  *                  rows), at least "burst_min_rows" rows (default 4) and "burst_min_bytes" stream
- *                  bytes (default 8 MiB), no tile dense in small spans (see "small_pieces"), and, for
- *                  a decode into tensors, every tensor's address aligned alike (mod 16) relative to
- *                  its stream offset.  The variant keeps reads and writes apart in time: reader
+ *                  bytes (default 8 MiB), at most one tile in a hundred dense in small spans (see
+ *                  "small_pieces"), and, for a decode into tensors, every tensor's address aligned
+ *                  alike (mod 16) relative to its stream offset; reft_reconstruct uses it under
+ *                  the first two conditions.  The variant keeps reads and writes apart in time: reader
  *                  waves XOR "burst_stage_bytes" (default 32768; a multiple of 4096, at most 65536)
  *                  of the stream at a time into LDS, and one writer wave per workgroup stores the
  *                  previous stage once all workgroups of the (persistent, "burst_wgs_per_cu" per

@@ -202,9 +202,9 @@ struct reft_plan {
     // stands in for the zero extension of the last segment
     std::map<uint64_t, reft_plan *> derived;
     void *zeros = nullptr;
-    // write-burst kernel: most spans that start in one tile (dense tiles keep the ordinary kernel)
-    // and a ring of counter blocks, one per launch in flight
-    uint32_t max_tile_spans = 0;
+    // write-burst kernel: spans that start in each tile, sorted (plans with many tiles dense in
+    // small spans keep the ordinary kernel), and a ring of counter blocks, one per launch in flight
+    std::vector<uint32_t> tile_spans_sorted;
     uint32_t *burst_ctr = nullptr;
     uint32_t burst_next = 0;
 
@@ -416,10 +416,12 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
             while (p->off[i + 1] <= o) ++i;      // o < L = off[T] keeps i < T
             first[t] = (uint32_t)i;
         }
+        p->tile_spans_sorted.resize(p->ntiles);
         for (uint64_t t = 0; t < p->ntiles; ++t) {
             const uint64_t nxt = t + 1 < p->ntiles ? first[t + 1] : T - 1;
-            if (nxt - first[t] > p->max_tile_spans) p->max_tile_spans = (uint32_t)(nxt - first[t]);
+            p->tile_spans_sorted[t] = (uint32_t)(nxt - first[t]);
         }
+        std::sort(p->tile_spans_sorted.begin(), p->tile_spans_sorted.end());
     }
 
     if (g_host_only.load()) {
@@ -965,6 +967,13 @@ static BurstCfg burst_cfg(uint32_t *ring, uint32_t slot, int num_cus)
     return bc;
 }
 
+// Tiles of the plan in which at least `small_pieces` spans start.
+static uint64_t dense_tiles(const reft_plan *p, uint32_t small_pieces)
+{
+    const auto &v = p->tile_spans_sorted;
+    return (uint64_t)(v.end() - std::lower_bound(v.begin(), v.end(), small_pieces));
+}
+
 static bool burst_wanted(uint32_t nrows, uint64_t L)
 {
     return nrows <= (uint32_t)kMaxSrc && g_burst.load() && nrows >= g_burst_min_rows.load() &&
@@ -992,11 +1001,12 @@ static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const
     const uint64_t *dtab = dst_row ? tab + (uint64_t)nrows * T : nullptr;
     const LaunchCfg cfg = launch_cfg(p);
     const PlanTables pt = p->tables();
-    // One pass over many rows: reads and writes are separated in time by the burst kernel (plans
-    // with tiles dense in small spans keep the ordinary kernel, whose LDS-staged path serves those
-    // better; so do ragged destinations whose spans are not all aligned alike relative to their
-    // stream offsets, which the burst kernel's staging image cannot represent).
-    if (burst_wanted(nrows, p->L) && p->max_tile_spans < cfg.small_pieces) {
+    // One pass over many rows: reads and writes are separated in time by the burst kernel.  It
+    // walks a stage piece by piece, which is slow where many small spans lie together (the ordinary
+    // kernel's LDS-staged path serves those better): plans with more than one such tile in a
+    // hundred keep the ordinary kernel.  So do ragged destinations whose spans are not all
+    // aligned alike relative to their stream offsets, which the staging image cannot represent.
+    if (burst_wanted(nrows, p->L) && dense_tiles(p, cfg.small_pieces) * 100 <= p->ntiles) {
         uint64_t vb = (uint64_t)(uintptr_t)dst_contig;
         bool alike = true;
         if (dst_row) {

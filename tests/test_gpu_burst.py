@@ -242,3 +242,25 @@ def test_decode_from_packed_streams(dev, L, k, phase):
     r = raw.cpu().numpy()
     assert np.array_equal(r[GUARD + phase:GUARD + phase + L], want)
     assert np.all(r[:GUARD + phase] == CANARY) and np.all(r[GUARD + phase + L:] == CANARY)
+
+
+def test_a_few_dense_tiles_among_large_spans(dev):
+    """Default thresholds: clusters of tiny tensors between large ones (fewer than one tile in a
+    hundred is dense in small spans, so the burst kernel walks those stages piece by piece)."""
+    reft.reft_set_tunable("burst_min_rows", 4)
+    reft.reft_set_tunable("burst_min_bytes", 8 << 20)
+    reft.reft_set_tunable("small_pieces", 8)
+    rng = np.random.default_rng(11)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(11)
+    sizes = []
+    for _ in range(3):
+        sizes += [24 << 20] + [int(x) for x in rng.integers(1, 3000, size=20)]
+    shards, keep = [], []
+    for s in range(4):
+        arena, spans = spans_in_arena(sizes, [0] * len(sizes), dev, gen)
+        keep.append(arena)
+        shards.append(spans)
+    par = check_encode(dev, shards, sizes)
+    offs = np.concatenate([[0], np.cumsum(sizes)])
+    check_decode(dev, shards, sizes, par, 1, [int(o % 16) for o in offs[:-1]])
