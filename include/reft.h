@@ -291,8 +291,8 @@ int reft_restore_wait(reft_plan *plan);
  *                  small-piece path of the gather / scatter kernels (default 8; 4294967295 = never,
  *                  0 = always).
  *   "burst"        1 (default) = reft_parity_encode, reft_reconstruct_spans and the rotated calls use
- *                  the write-burst variant of the XOR kernel where it applies: one pass (at most 8
- *                  rows), at least "burst_min_rows" rows (default 4) and "burst_min_bytes" stream
+ *                  the write-burst variant of the XOR kernel where it applies: a pass (up to 8 rows
+ *                  each) of at least "burst_min_rows" rows (default 4), "burst_min_bytes" stream
  *                  bytes (default 8 MiB), at most one tile in a hundred dense in small spans (see
  *                  "small_pieces"), and, for a decode into tensors, every tensor's address aligned
  *                  alike (mod 16) relative to its stream offset; reft_reconstruct uses it under

@@ -974,11 +974,6 @@ static uint64_t dense_tiles(const reft_plan *p, uint32_t small_pieces)
     return (uint64_t)(v.end() - std::lower_bound(v.begin(), v.end(), small_pieces));
 }
 
-static bool burst_wanted(uint32_t nrows, uint64_t L)
-{
-    return nrows <= (uint32_t)kMaxSrc && g_burst.load() && nrows >= g_burst_min_rows.load() &&
-           L >= g_burst_min_bytes.load();
-}
 
 // XOR of `nrows` rows of span pointers (row stride T of plan p) into a contiguous destination or,
 // if dst_row is given, into the destination's own spans.  More than kMaxSrc rows are folded in
@@ -1001,27 +996,21 @@ static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const
     const uint64_t *dtab = dst_row ? tab + (uint64_t)nrows * T : nullptr;
     const LaunchCfg cfg = launch_cfg(p);
     const PlanTables pt = p->tables();
-    // One pass over many rows: reads and writes are separated in time by the burst kernel.  It
-    // walks a stage piece by piece, which is slow where many small spans lie together (the ordinary
+    // Passes over many rows separate reads and writes in time with the burst kernel.  It walks a
+    // stage piece by piece, which is slow where many small spans lie together (the ordinary
     // kernel's LDS-staged path serves those better): plans with more than one such tile in a
     // hundred keep the ordinary kernel.  So do ragged destinations whose spans are not all
     // aligned alike relative to their stream offsets, which the staging image cannot represent.
-    if (burst_wanted(nrows, p->L) && dense_tiles(p, cfg.small_pieces) * 100 <= p->ntiles) {
-        uint64_t vb = (uint64_t)(uintptr_t)dst_contig;
-        bool alike = true;
-        if (dst_row) {
-            bool have = false;
-            for (uint64_t t = 0; t < T && alike; ++t) {
-                if (p->off[t + 1] == p->off[t]) continue;
-                const uint64_t c = ((uint64_t)(uintptr_t)dst_row[t] - p->off[t]) & 15u;
-                if (!have) { vb = c; have = true; }
-                else alike = c == vb;
-            }
-        }
-        if (alike) {
-            const BurstCfg bc = burst_cfg(p->burst_ctr, p->burst_next++, p->num_cus);
-            HIPCHK(launch_gather_burst(pt, tab, (int)nrows, dtab, vb, 0, p->L, cfg, bc, s));
-            return record(p->ring_ev[entry], s);
+    uint64_t vb = (uint64_t)(uintptr_t)dst_contig;
+    bool burst_ok = g_burst.load() && p->L >= g_burst_min_bytes.load() &&
+                    dense_tiles(p, cfg.small_pieces) * 100 <= p->ntiles;
+    if (burst_ok && dst_row) {
+        bool have = false;
+        for (uint64_t t = 0; t < T && burst_ok; ++t) {
+            if (p->off[t + 1] == p->off[t]) continue;
+            const uint64_t c = ((uint64_t)(uintptr_t)dst_row[t] - p->off[t]) & 15u;
+            if (!have) { vb = c; have = true; }
+            else burst_ok = c == vb;
         }
     }
     uint32_t done = 0;
@@ -1030,8 +1019,14 @@ static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const
         uint32_t n = nrows - done;
         const uint32_t cap = (uint32_t)kMaxSrc - (acc ? 1u : 0u);
         if (n > cap) n = cap;
-        HIPCHK(launch_gather(pt, tab + (uint64_t)done * T, (int)n, acc, dtab,
-                             (uint64_t)(uintptr_t)dst_contig, 0, p->L, cfg, s));
+        if (burst_ok && n + (acc ? 1u : 0u) >= g_burst_min_rows.load()) {
+            const BurstCfg bc = burst_cfg(p->burst_ctr, p->burst_next++, p->num_cus);
+            HIPCHK(launch_gather_burst(pt, tab + (uint64_t)done * T, (int)n, acc, dtab, vb, 0, p->L,
+                                       cfg, bc, s));
+        } else {
+            HIPCHK(launch_gather(pt, tab + (uint64_t)done * T, (int)n, acc, dtab,
+                                 (uint64_t)(uintptr_t)dst_contig, 0, p->L, cfg, s));
+        }
         done += n;
     }
     return record(p->ring_ev[entry], s);
@@ -1254,40 +1249,45 @@ extern "C" int reft_reconstruct(const void *const *shards, uint32_t k, const voi
     const LaunchCfg cfg = launch_cfg(nullptr);
     const uint32_t tile_shift = (uint32_t)g_tile_shift.load();
     hipStream_t st = (hipStream_t)stream;
-    if (burst_wanted(n, L)) {
-        // one pass: reads and writes separated in time (counter blocks from a ring per device,
-        // allocated on first use and kept until the process ends)
+    BurstCfg bc{};
+    const bool burst_ok = g_burst.load() && L >= g_burst_min_bytes.load();
+    uint32_t *ring = nullptr;
+    int num_cus = 256;
+    if (burst_ok) {
+        // counter blocks from a ring per device, allocated on first use and kept until the
+        // process ends
         static std::mutex mu;
         static std::map<int, std::pair<uint32_t *, int>> rings;   // device -> (ring, compute units)
-        static uint32_t next_slot = 0;
         int dev = 0;
         HIPCHK(hipGetDevice(&dev));
-        BurstCfg bc;
-        {
-            std::lock_guard<std::mutex> lock(mu);
-            auto it = rings.find(dev);
-            if (it == rings.end()) {
-                uint32_t *ring = nullptr;
-                hipDeviceProp_t prop;
-                HIPCHK(hipGetDeviceProperties(&prop, dev));
-                HIPCHK(hipMalloc((void **)&ring, kCtrBlocks * kBurstCtrBytes));
-                it = rings.emplace(dev, std::make_pair(ring, prop.multiProcessorCount > 0
-                                                                 ? prop.multiProcessorCount : 256)).first;
-            }
-            bc = burst_cfg(it->second.first, next_slot++, it->second.second);
+        std::lock_guard<std::mutex> lock(mu);
+        auto it = rings.find(dev);
+        if (it == rings.end()) {
+            uint32_t *r = nullptr;
+            hipDeviceProp_t prop;
+            HIPCHK(hipGetDeviceProperties(&prop, dev));
+            HIPCHK(hipMalloc((void **)&r, kCtrBlocks * kBurstCtrBytes));
+            it = rings.emplace(dev, std::make_pair(r, prop.multiProcessorCount > 0
+                                                          ? prop.multiProcessorCount : 256)).first;
         }
-        SrcBases b{};
-        for (uint32_t j = 0; j < n; ++j) b.p[j] = src[j];
-        HIPCHK(launch_xor_contig_burst(b, (int)n, (uint64_t)(uintptr_t)out_dev, L, cfg, bc, st));
-        return REFT_OK;
+        ring = it->second.first;
+        num_cus = it->second.second;
     }
+    static std::atomic<uint32_t> next_slot{0};
     uint32_t done = 0;
     while (done < n) {
         SrcBases b{};
         int m = 0;
         if (done > 0) b.p[m++] = (uint64_t)(uintptr_t)out_dev;     // fold into the partial result
         while (m < kMaxSrc && done < n) b.p[m++] = src[done++];
-        HIPCHK(launch_xor_contig(b, m, (uint64_t)(uintptr_t)out_dev, L, tile_shift, cfg, st));
+        if (burst_ok && (uint32_t)m >= g_burst_min_rows.load()) {
+            // reads and writes separated in time; folding in place is safe: a stage of the
+            // output is read and, a round later, written by the same workgroup only
+            bc = burst_cfg(ring, next_slot++, num_cus);
+            HIPCHK(launch_xor_contig_burst(b, m, (uint64_t)(uintptr_t)out_dev, L, cfg, bc, st));
+        } else {
+            HIPCHK(launch_xor_contig(b, m, (uint64_t)(uintptr_t)out_dev, L, tile_shift, cfg, st));
+        }
     }
     return REFT_OK;
     REFT_GUARD_END("reft_reconstruct")

@@ -50,11 +50,11 @@ hipError_t launch_gather(const PlanTables &pt, const uint64_t *tab, int nrows, b
                          const uint64_t *dtab, uint64_t dst_vbase, uint64_t lo, uint64_t hi,
                          const LaunchCfg &cfg, hipStream_t stream);
 
-// The same result as launch_gather with acc = false, by the burst kernel.  With dtab == null the
-// destination is contiguous and vb its virtual base.  With dtab, every span with bytes must
+// The same result as launch_gather, by the burst kernel.  With dtab == null the destination is
+// contiguous and vb its virtual base.  With dtab, every span with bytes must
 // satisfy (dtab[i] - off[i]) mod 16 == vb mod 16 (the caller checks; otherwise use launch_gather).
 // stage_bytes: a multiple of 4096, at most 65536.
-hipError_t launch_gather_burst(const PlanTables &pt, const uint64_t *tab, int nrows,
+hipError_t launch_gather_burst(const PlanTables &pt, const uint64_t *tab, int nrows, bool acc,
                                const uint64_t *dtab, uint64_t vb, uint64_t lo, uint64_t hi,
                                const LaunchCfg &cfg, const BurstCfg &bc, hipStream_t stream);
 

@@ -515,7 +515,7 @@ __device__ __forceinline__ void burst_rounds(uint64_t nstages, uint32_t stage, u
 template <int K, int U, bool NT>
 __global__ void __launch_bounds__(kBurstThreads)
 k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *__restrict__ dtab,
-               uint64_t vb, uint64_t lo, uint64_t hi, uint32_t stage, uint32_t *ctr,
+               uint64_t vb, uint64_t lo, uint64_t hi, uint32_t acc, uint32_t stage, uint32_t *ctr,
                uint32_t max_polls, uint32_t nap)
 {
     const uint64_t nstages = (hi - lo + stage - 1) / stage;
@@ -535,7 +535,11 @@ k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *
                 if (pe > e) pe = e;
                 uint64_t s[K];
 #pragma unroll
-                for (int j = 0; j < K; ++j) s[j] = tab[(uint64_t)j * pt.T + i] + (o - so);
+                for (int j = 0; j < K - 1; ++j) s[j] = tab[(uint64_t)j * pt.T + i] + (o - so);
+                // accumulate mode: the destination's current bytes are the last source (a stage
+                // of the destination is read and, a round later, written by this workgroup only)
+                s[K - 1] = !acc ? tab[(uint64_t)(K - 1) * pt.T + i] + (o - so)
+                                : dtab ? dtab[i] + (o - so) : vb + o;
                 xor_piece<K, U, NT, ToImage>(vb + o, s, (uint32_t)(pe - o), sink);
                 o = pe;
             }
@@ -730,15 +734,16 @@ static hipError_t burst_grid(const void *fn, uint64_t nstages, const LaunchCfg &
     return hipSuccess;
 }
 
-hipError_t launch_gather_burst(const PlanTables &pt, const uint64_t *tab, int nrows,
+hipError_t launch_gather_burst(const PlanTables &pt, const uint64_t *tab, int nrows, bool acc,
                                const uint64_t *dtab, uint64_t vb, uint64_t lo, uint64_t hi,
                                const LaunchCfg &cfg, const BurstCfg &bc, hipStream_t stream)
 {
     if (lo >= hi) return hipSuccess;
     if (hi > pt.L || !burst_cfg_ok(bc)) return hipErrorInvalidValue;
     void (*fn)(PlanTables, const uint64_t *, const uint64_t *, uint64_t, uint64_t, uint64_t, uint32_t,
-               uint32_t *, uint32_t, uint32_t) = nullptr;
-    REFT_PICK_K(k_gather_burst, fn, nrows)
+               uint32_t, uint32_t *, uint32_t, uint32_t) = nullptr;
+    const int nsrc = nrows + (acc ? 1 : 0);
+    REFT_PICK_K(k_gather_burst, fn, nsrc)
     size_t lds = 0;
     uint32_t grid = 0;
     const uint64_t nstages = (hi - lo + bc.stage_bytes - 1) / bc.stage_bytes;
@@ -746,7 +751,7 @@ hipError_t launch_gather_burst(const PlanTables &pt, const uint64_t *tab, int nr
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(256), 0, stream, bc.ctr, 9 * kCtrStride);
     hipLaunchKernelGGL(fn, dim3(grid), dim3(kBurstThreads), lds, stream, pt, tab, dtab, vb, lo, hi,
-                       bc.stage_bytes, bc.ctr, bc.max_polls, bc.nap);
+                       acc ? 1u : 0u, bc.stage_bytes, bc.ctr, bc.max_polls, bc.nap);
     return hipGetLastError();
 }
 

@@ -137,8 +137,8 @@ def test_edge_sizes_and_misalignment(dev, sizes, phase_mode):
         check_decode(dev, shards, sizes, par, lost, [int(x) for x in rng.integers(0, 16, size=len(sizes))])
 
 
-@pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 6, 7, 8])
-def test_every_source_count_of_one_launch(dev, k):
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 15, 16, 23, 31])
+def test_every_source_count_of_one_launch_and_chained_passes(dev, k):
     wl = make_workload(0)
     shards = [fill_shard(wl, s % wl.k, dev) for s in range(k)]
     par = check_encode(dev, shards, span_nbytes(wl))
@@ -218,7 +218,7 @@ def test_same_result_as_the_ordinary_kernel_and_back_to_back(dev):
 
 
 @pytest.mark.parametrize("L", [1, 15, 16, 17, 4096, 32767, 32768, 32769, 100003, (1 << 20) + 5, 3 * (1 << 20)])
-@pytest.mark.parametrize("k,phase", [(1, 0), (3, 0), (4, 5), (7, 11)])
+@pytest.mark.parametrize("k,phase", [(1, 0), (3, 0), (4, 5), (7, 11), (9, 3), (16, 0), (31, 7)])
 def test_decode_from_packed_streams(dev, L, k, phase):
     """reft_reconstruct (contiguous survivors, parity and output) through the burst variant of the
     contiguous XOR kernel: every source count of one pass, odd addresses, ragged last stage."""
