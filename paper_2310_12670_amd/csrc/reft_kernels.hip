@@ -17,6 +17,7 @@
 
 #include <map>
 #include <mutex>
+#include <tuple>
 #include <utility>
 
 namespace reft {
@@ -696,16 +697,19 @@ hipError_t launch_gather(const PlanTables &pt, const uint64_t *tab, int nrows, b
 static hipError_t burst_occupancy(const void *fn, size_t lds, int *per_cu)
 {
     static std::mutex mu;
-    static std::map<std::pair<const void *, size_t>, int> known;
+    static std::map<std::tuple<int, const void *, size_t>, int> known;   // per device
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
     std::lock_guard<std::mutex> lock(mu);
-    auto it = known.find({fn, lds});
+    auto it = known.find(std::make_tuple(dev, fn, lds));
     if (it == known.end()) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         int n = 0;
         e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, kBurstThreads, lds);
         if (e != hipSuccess) return e;
-        it = known.emplace(std::make_pair(fn, lds), n).first;
+        it = known.emplace(std::make_tuple(dev, fn, lds), n).first;
     }
     *per_cu = it->second;
     return hipSuccess;
