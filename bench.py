@@ -292,8 +292,10 @@ def main() -> int:
         return round(100.0 * x / peak, 1)
 
     def measure_stages():
-        def timed_alone(fn, stream, reps=5):
-            fn()
+        def timed_alone(fn, stream, reps=20, warm=3):
+            """Median of `reps` timed repetitions after `warm` untimed ones."""
+            for _ in range(warm):
+                fn()
             torch.cuda.synchronize()
             ts = []
             for _ in range(reps):
@@ -336,8 +338,8 @@ def main() -> int:
             s_h2d.wait_stream(s_xor)
             reft.reft_restore(plan, host_snap, stag_load, p_fresh_own, s_h2d, s_load)
             s_xor.wait_stream(s_load)
-        t_snap = timed_alone(snap, s_xor, reps=3)
-        t_rest = timed_alone(rest, s_xor, reps=3)
+        t_snap = timed_alone(snap, s_xor, reps=5, warm=1)
+        t_rest = timed_alone(rest, s_xor, reps=5, warm=1)
 
         stages = {
             "pack_kernel_GBps": round(2 * L / t_pack / 1e9, 1),
