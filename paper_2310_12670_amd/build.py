@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -10,7 +11,38 @@ LIB = os.path.join(HERE, "libreft.so")
 SOURCES = ["reft_api.hip", "reft_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
          # keep packed-FP32 instruction selection off for every kernel in the library
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # per-kernel register counts, checked below
+         "-Rpass-analysis=kernel-resource-usage"]
+
+# The write-burst kernels run two 5-wave workgroups per compute unit, all resident at once.  Measured
+# on gfx950: with more than 128 vector registers per lane only one such workgroup fits (four waves
+# of two workgroups can land on one SIMD: 4 x 128 = its 512 registers), the second half of the
+# grid then runs after the first, and the bursts lose their timing.
+BURST_KERNELS = ("k_gather_burst", "k_xor_contig_burst")
+BURST_MAX_VGPRS = 128
+
+
+def check_burst_registers(compiler_output: str) -> dict:
+    """VGPR count per burst-kernel instantiation from the compiler's resource remarks; raises if
+    one exceeds the residency limit or if no such kernel was reported."""
+    counts = {}
+    name = None
+    for line in compiler_output.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+            continue
+        m = re.search(r"\bVGPRs: (\d+)", line)
+        if m and name and any(k in name for k in BURST_KERNELS):
+            counts[name] = int(m.group(1))
+    if not counts:
+        raise RuntimeError("no register report for the burst kernels in the compiler output")
+    over = {n: v for n, v in counts.items() if v > BURST_MAX_VGPRS}
+    if over:
+        raise RuntimeError("burst kernels over %d VGPRs (one workgroup per compute unit only): %s"
+                           % (BURST_MAX_VGPRS, over))
+    return counts
 
 
 def build(verbose: bool = False) -> str:
@@ -20,8 +52,10 @@ def build(verbose: bool = False) -> str:
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout)
-    if verbose and res.stdout.strip():
-        print(res.stdout)
+    counts = check_burst_registers(res.stdout)
+    if verbose:
+        print("\n".join(l for l in res.stdout.splitlines() if "remark:" not in l))
+        print("burst kernels: %d instantiations, at most %d VGPRs" % (len(counts), max(counts.values())))
     return LIB
 
 

@@ -428,7 +428,8 @@ k_gather(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *__rest
 // 16-byte chunks of every destination span.
 //
 // ctr: 9 counters kCtrStride words apart, all zero at launch.  Workgroups arrive on counter
-// (blockIdx.x & 7); the last arrival of a group for a round bumps counter 8, the only one polled.
+// (blockIdx.x & 7); every arrival that completes a multiple of the group's size bumps counter 8,
+// the only one polled, so counter 8 tells how many rounds the groups have completed between them.
 // ------------------------------------------------------------------------------------------------
 constexpr int kBurstThreads = kThreads + 64;
 constexpr uint32_t kCtrStride = 64;
@@ -506,7 +507,7 @@ __device__ __forceinline__ void burst_rounds(uint64_t nstages, uint32_t stage, u
         if (writer && lane == 0 && r < rounds && max_polls) {
             const uint32_t old = __hip_atomic_fetch_add(ctr + g * kCtrStride, 1u, __ATOMIC_RELAXED,
                                                         __HIP_MEMORY_SCOPE_AGENT);
-            if (old + 1 == ((uint32_t)r + 1) * members)
+            if ((old + 1) % members == 0)     // whichever round the arriving workgroup is in
                 __hip_atomic_fetch_add(ctr + 8 * kCtrStride, 1u, __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
         }

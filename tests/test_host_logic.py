@@ -201,3 +201,21 @@ def test_plans_of_the_five_configurations(host_only):
                 assert all((1 << 20) <= b <= (1 << 27) for b in wl.bucket_nbytes[:-1])
         finally:
             reft.reft_plan_destroy(plan)
+
+
+def test_build_refuses_burst_kernels_that_need_too_many_registers():
+    """Two 5-wave workgroups of a burst kernel fit on a compute unit only up to 128 vector
+    registers per lane; the build reads the compiler's resource remarks and fails beyond that."""
+    from paper_2310_12670_amd.build import check_burst_registers
+
+    def remarks(name, vgprs):
+        return (f"x.hip:1:1: remark: Function Name: {name} [-Rpass-analysis=kernel-resource-usage]\n"
+                f"x.hip:1:1: remark:     SGPRs: 100 [-Rpass-analysis=kernel-resource-usage]\n"
+                f"x.hip:1:1: remark:     VGPRs: {vgprs} [-Rpass-analysis=kernel-resource-usage]\n")
+
+    ok = remarks("_ZN4reft14k_gather_burstILi8ELi4ELb1EEEvX", 121) + remarks("_ZN4reft8k_gatherILi8ELi4ELb1EEEvX", 167)
+    assert check_burst_registers(ok) == {"_ZN4reft14k_gather_burstILi8ELi4ELb1EEEvX": 121}
+    with pytest.raises(RuntimeError):
+        check_burst_registers(ok + remarks("_ZN4reft18k_xor_contig_burstILi8ELi4ELb1EEEvX", 129))
+    with pytest.raises(RuntimeError):
+        check_burst_registers(remarks("_ZN4reft8k_gatherILi8ELi4ELb1EEEvX", 167))   # no burst kernel reported
