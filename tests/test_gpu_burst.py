@@ -264,3 +264,32 @@ def test_a_few_dense_tiles_among_large_spans(dev):
     par = check_encode(dev, shards, sizes)
     offs = np.concatenate([[0], np.cumsum(sizes)])
     check_decode(dev, shards, sizes, par, 1, [int(o % 16) for o in offs[:-1]])
+
+
+def test_concurrent_launches_on_several_streams(dev):
+    """Burst kernels of three plans queued on three streams at once: their persistent grids cannot
+    all be resident together, so the timing of the bursts breaks down - the bytes must not."""
+    reft.reft_set_tunable("burst_min_rows", 4)
+    reft.reft_set_tunable("burst_min_bytes", 8 << 20)
+    reft.reft_set_tunable("small_pieces", 8)
+    wl = make_workload(2, shrink=4, layers=2)
+    sizes = span_nbytes(wl)
+    shards = [fill_shard(wl, s, dev) for s in range(wl.k)]
+    flat = [t for sh in shards for t in sh]
+    streams = [oracle.pack([oracle.as_bytes(t.cpu()) for t in sh]) for sh in shards]
+    want = oracle.encode(streams)
+    plans = [reft.reft_plan_create(sizes) for _ in range(3)]
+    sts = [torch.cuda.Stream() for _ in range(3)]
+    outs = [[torch.empty(wl.L, dtype=torch.uint8, device=dev) for _ in range(4)] for _ in range(3)]
+    try:
+        torch.cuda.synchronize()
+        for rep in range(4):
+            for p, s, o in zip(plans, sts, outs):
+                reft.reft_parity_encode(p, flat, wl.k, o[rep], s)
+        torch.cuda.synchronize()
+    finally:
+        for p in plans:
+            reft.reft_plan_destroy(p)
+    for o in outs:
+        for t in o:
+            assert np.array_equal(t.cpu().numpy(), want)
