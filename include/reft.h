@@ -292,7 +292,7 @@ int reft_restore_wait(reft_plan *plan);
  *                  0 = always).
  *   "burst"        1 (default) = reft_parity_encode, reft_reconstruct_spans and the rotated calls use
  *                  the write-burst variant of the XOR kernel where it applies: a pass (up to 8 rows
- *                  each) of at least "burst_min_rows" rows (default 4), "burst_min_bytes" stream
+ *                  each) of at least "burst_min_rows" rows (default 5), "burst_min_bytes" stream
  *                  bytes (default 8 MiB), at most one tile in a hundred dense in small spans (see
  *                  "small_pieces"), and, for a decode into tensors, every tensor's address aligned
  *                  alike (mod 16) relative to its stream offset; reft_reconstruct uses it under

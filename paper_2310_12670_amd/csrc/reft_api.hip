@@ -59,7 +59,7 @@ static std::atomic<uint64_t> g_dma_min{65536};   // pieces of at least this many
 static std::atomic<uint64_t> g_gather_min{8};    // shortest run of smaller pieces worth a gather kernel
 static std::atomic<uint64_t> g_dma_streams{1};   // 2 = piece copies alternate with a helper stream
 static std::atomic<uint64_t> g_burst{1};         // parity encode may use the write-burst kernel
-static std::atomic<uint64_t> g_burst_min_rows{4};    // ... from this many sources on
+static std::atomic<uint64_t> g_burst_min_rows{5};    // ... from this many sources on
 static std::atomic<uint64_t> g_burst_min_bytes{8ull << 20};  // ... and from this stream length on
 static std::atomic<uint64_t> g_burst_stage{32768};   // stream bytes per workgroup and round
 static std::atomic<uint64_t> g_burst_wgs{2};         // resident workgroups per compute unit
