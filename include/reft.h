@@ -114,6 +114,10 @@ int reft_plan_split(const reft_plan *plan, double t_bubble, double t_ss, uint64_
  *       bubbles, recovery): kernels that keep the link's write path full slow down kernels
  *       running beside them.  host_dst must be device-accessible pinned memory (hipHostMalloc),
  *       else REFT_EINVAL.
+ * Streams: the HIP runtime maps streams onto a few hardware queues (4 per process by default) in
+ * the order in which they first get work, and two streams on one queue run in turn.  A snapshot
+ * and a restore only overlap on the link (full duplex) if their copy streams sit on different
+ * queues: give each its own stream and let both do some work early, in a fixed order.
  * After the last bucket a completion event is recorded (see reft_snapshot_wait): the snapshot is
  * complete only when every bucket has landed (section 4.4: COMPLETED when all tensors are
  * snapshotted).  Postcondition: host_dst[0..L) == stream; host_dst[L..) untouched.
