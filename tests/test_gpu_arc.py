@@ -1,0 +1,52 @@
+"""Redundant copying (section 4.2, ARC) needs no kernel of its own: each member snapshots its own
+shard and a peer's, and a lost member's shard is restored from the peer's duplicate.  GPU parity of
+that composition of reft_snapshot_pack and reft_restore against the CPU oracle, bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2310_12670_amd as reft
+from workload import fill_shard, make_workload, span_nbytes
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("staged", [True, False])
+def test_every_member_is_restored_from_its_duplicate(staged):
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = make_workload(0)
+    k, L = wl.k, wl.L
+    sizes = span_nbytes(wl)
+    shards = [fill_shard(wl, s, dev) for s in range(k)]
+    streams = [oracle.pack_bucketed([oracle.as_bytes(t.cpu()) for t in sh], wl.bucket_nbytes) for sh in shards]
+    plan = reft.reft_plan_create(sizes, wl.bucket_nbytes)
+    try:
+        slot = reft.reft_plan_staging_slot_bytes(plan)
+        staging = torch.empty(2 * slot, dtype=torch.uint8, device=dev) if staged else None
+        s_a, s_b = torch.cuda.Stream(), torch.cuda.Stream()
+        # member i holds host copies of shard i and of shard (i + 1) mod k: twice the snapshot volume
+        own = [torch.empty(L, dtype=torch.uint8, pin_memory=True) for _ in range(k)]
+        dup = [torch.empty(L, dtype=torch.uint8, pin_memory=True) for _ in range(k)]
+        for i in range(k):
+            reft.reft_snapshot_pack(plan, shards[i], staging, own[i], s_a, s_b)
+            reft.reft_snapshot_wait(plan)
+            reft.reft_snapshot_pack(plan, shards[(i + 1) % k], staging, dup[i], s_a, s_b)
+            reft.reft_snapshot_wait(plan)
+        assert sum(b.numel() for b in own) + sum(b.numel() for b in dup) == 2 * k * L
+        for i in range(k):
+            assert np.array_equal(own[i].numpy(), streams[i])
+            assert np.array_equal(dup[i].numpy(), streams[(i + 1) % k])
+        # every possible lost member: its host copies are gone, member lost-1 holds its duplicate
+        for lost in range(k):
+            holder = (lost - 1) % k
+            fresh = [torch.zeros_like(t) for t in shards[lost]]
+            reft.reft_restore(plan, dup[holder], staging, fresh, s_b, s_a)
+            reft.reft_restore_wait(plan)
+            want = oracle.unpack(streams[lost], sizes)
+            for t, w in zip(fresh, want):
+                assert np.array_equal(oracle.as_bytes(t.cpu()), w), f"member {lost} from member {holder}"
+    finally:
+        reft.reft_plan_destroy(plan)
