@@ -219,3 +219,20 @@ def test_build_refuses_burst_kernels_that_need_too_many_registers():
         check_burst_registers(ok + remarks("_ZN4reft18k_xor_contig_burstILi8ELi4ELb1EEEvX", 129))
     with pytest.raises(RuntimeError):
         check_burst_registers(remarks("_ZN4reft8k_gatherILi8ELi4ELb1EEEvX", 167))   # no burst kernel reported
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/reft.h is the boundary: it must compile as C99 and as C++ with no other header of
+    the project."""
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "t.c"
+    src.write_text('#include "reft.h"\nint main(void) { return reft_version() == 0; }\n')
+    inc = os.path.join(root, "include")
+    if shutil.which("gcc"):
+        subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                        "-I", inc, str(src)], check=True)
+    if shutil.which("g++"):
+        subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++",
+                        "-I", inc, str(src)], check=True)
