@@ -82,6 +82,9 @@ def main() -> int:
                          "known size that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--overlap-encode", action="store_true",
                     help="start the own shard's snapshot first and run the parity encode beside it")
+    ap.add_argument("--graph-copies", type=int, default=-1, choices=[-1, 0, 1, 2],
+                    help="tunable graph_copies: staged piece copies as a replayed hipGraph "
+                         "(0 off, 1 independent nodes, 2 chain)")
     ap.add_argument("--no-burst", action="store_true",
                     help="XOR kernels without write bursts (the ordinary gather kernel), for comparison")
     ap.add_argument("--burst-polls", type=int, default=-1,
@@ -166,6 +169,8 @@ def main() -> int:
         reft.reft_set_tunable("dma_streams", args.dma_streams)
     if args.no_burst:
         reft.reft_set_tunable("burst", 0)
+    if args.graph_copies >= 0:
+        reft.reft_set_tunable("graph_copies", args.graph_copies)
     if args.burst_polls >= 0:
         reft.reft_set_tunable("burst_max_polls", args.burst_polls)
     if args.burst_nap >= 0:

@@ -54,7 +54,9 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + res.stdout)
     counts = check_burst_registers(res.stdout)
     if verbose:
-        print("\n".join(l for l in res.stdout.splitlines() if "remark:" not in l))
+        # the resource remarks and the source lines they quote are not worth showing
+        print("\n".join(l for l in res.stdout.splitlines()
+                        if "remark:" not in l and not re.match(r"\s*\d*\s*\|", l)))
         print("burst kernels: %d instantiations, at most %d VGPRs" % (len(counts), max(counts.values())))
     return LIB
 

@@ -152,3 +152,45 @@ def test_completed_and_ongoing_snapshots(dev):
             reft.reft_ckpt_destroy(ck)
     finally:
         reft.reft_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("mode", [1, 2, 0])
+def test_replayed_copy_graphs_follow_the_data(dev, mode):
+    """The staged transport replays its piece copies as a cached hipGraph when a call repeats the
+    same tensors and host buffer.  Every replay must move the tensors' current bytes: the data is
+    changed between snapshots, eager work and synchronisations lie between the replays, and each
+    snapshot and each restore is compared with the oracle."""
+    saved = {n: reft.reft_get_tunable(n) for n in ("graph_copies", "dma_min_bytes")}
+    reft.reft_set_tunable("graph_copies", mode)
+    reft.reft_set_tunable("dma_min_bytes", 0)          # every piece is a copy of its own
+    try:
+        wl = make_workload(0)
+        sizes = span_nbytes(wl)
+        shard = fill_shard(wl, 0, dev)
+        plan = reft.reft_plan_create(sizes, wl.bucket_nbytes)
+        try:
+            slot = reft.reft_plan_staging_slot_bytes(plan)
+            staging = torch.empty(2 * slot, dtype=torch.uint8, device=dev)
+            host = torch.empty(wl.L, dtype=torch.uint8, pin_memory=True)
+            fresh = [torch.zeros_like(t) for t in shard]
+            s_a, s_b = torch.cuda.Stream(), torch.cuda.Stream()
+            for rep in range(5):
+                for t in shard:                          # new contents, same addresses
+                    t.view(torch.uint8).add_(rep + 1)
+                torch.cuda.synchronize()
+                want = oracle.pack_bucketed([oracle.as_bytes(t.cpu()) for t in shard], wl.bucket_nbytes)
+                reft.reft_snapshot_pack(plan, shard, staging, host, s_a, s_b)
+                reft.reft_snapshot_wait(plan)
+                assert np.array_equal(host.numpy(), want), f"snapshot {rep}"
+                for t in fresh:
+                    t.zero_()
+                torch.cuda.synchronize()
+                reft.reft_restore(plan, host, staging, fresh, s_b, s_a)
+                reft.reft_restore_wait(plan)
+                for t, w in zip(fresh, oracle.unpack(want, sizes)):
+                    assert np.array_equal(oracle.as_bytes(t.cpu()), w), f"restore {rep}"
+        finally:
+            reft.reft_plan_destroy(plan)
+    finally:
+        for n, v in saved.items():
+            reft.reft_set_tunable(n, v)

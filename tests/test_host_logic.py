@@ -162,7 +162,7 @@ def test_reconstruct_argument_checks_need_no_gpu():
 def test_tunables():
     for name, good, bad in (("unroll", 2, 3), ("nontemporal", 0, 2), ("tile_shift", 14, 40),
                             ("max_wgs", 64, 1 << 30), ("link_wgs", 8, 0), ("dma_streams", 2, 3),
-                            ("gather_min_pieces", 3, 0), ("small_pieces", 5, 1 << 40),
+                            ("gather_min_pieces", 3, 0), ("graph_copies", 2, 3), ("small_pieces", 5, 1 << 40),
                             ("burst", 0, 2), ("burst_min_rows", 2, 0),
                             ("burst_stage_bytes", 16384, 5000), ("burst_stage_bytes", 65536, 131072),
                             ("burst_wgs_per_cu", 3, 9), ("burst_max_polls", 0, 1 << 20),
