@@ -28,6 +28,11 @@
  *     addresses.  Pointer *arrays* (span_ptrs, shards) are host arrays holding device addresses.
  *   - The caller owns all data buffers, the staging ring, the pinned host buffer and the HIP
  *     streams.  The library owns only the plan (host tables, their device copies, events).
+ *   - Device and pinned memory is allocated by reft_plan_create, reft_ckpt_create and the first
+ *     rotated call for a given (k, member) only.  The data-moving calls allocate none and never
+ *     wait for the whole device; they block the calling thread only in one case: a call that
+ *     brings a pointer array the plan has not seen lately may have to wait for the kernels that
+ *     still read the cached table whose room it takes (see reft_plan_create).
  *   - The data-moving calls enqueue work on the given streams and return; results are complete
  *     when those streams (or reft_snapshot_wait / reft_restore_wait) have been synchronised.
  *     Source data must not be modified, and pointer arrays' targets not freed, before that.
@@ -50,6 +55,7 @@ extern "C" {
 #define REFT_ESIZE          (-2)  /* a buffer is too small or a length does not match the plan    */
 #define REFT_EHIP           (-3)  /* a HIP runtime call failed; text in reft_last_error()         */
 #define REFT_EUNRECOVERABLE (-4)  /* more than one shard lost: beyond what one parity can decode  */
+#define REFT_EBUSY          (-5)  /* the previous snapshot of a reft_ckpt has not been committed yet */
 
 #define REFT_MAX_K 32             /* most shards (or survivors + parity) in one call              */
 
@@ -67,7 +73,12 @@ typedef void *reft_stream;
  *                   (NB may be 0 only when L == 0).  With bucket_nbytes == NULL, NB == 0 and
  *                   uniform_bucket == 0 the whole stream is one bucket.
  * out               receives the plan; destroy it with reft_plan_destroy.
- * Allocates the plan's device tables and events on the current GPU (the only allocating call).
+ * Allocates on the current GPU everything the data-moving calls will need: the device tables, the
+ * events, the burst kernels' counters, the piece lists of the staged transport for the whole
+ * stream, and a cache for the callers' pointer arrays (72 rows of T pointers, pinned host mirror
+ * and device copy).  A call that passes pointers the cache already holds uploads nothing; up to
+ * 32 tables are kept, each remembering the streams (up to 4) that last read it, and a new table
+ * takes the room of the oldest ones after waiting for exactly those readers.
  * Errors: REFT_EINVAL (null out/span_nbytes, T == 0, a zero-length bucket), REFT_ESIZE (bucket
  * lengths do not sum to L), REFT_EHIP.
  */
@@ -92,6 +103,12 @@ int reft_plan_tile_first_span(const reft_plan *plan, uint64_t t, uint64_t *span)
 /* The index cut of SplitParameter (Algorithm 1): floor(n * t_bubble / t_ss) with n = L bytes,
  * clamped to [0, L]; t_ss must be > 0.  Returns the cut through *cut. */
 int reft_plan_split(const reft_plan *plan, double t_bubble, double t_ss, uint64_t *cut);
+/* What a staged snapshot (or restore) of the whole stream consists of under the current
+ * "dma_min_bytes" / "gather_min_pieces": *gather_launches kernel launches on pack_stream (runs of
+ * small pieces) and *copies hipMemcpyAsync calls on copy_stream.  With *gather_launches == 0 the
+ * transport is pure DMA, pack_stream carries no work, and the caller may pass one stream for both
+ * (one hardware queue less: see the note on streams under reft_snapshot_pack). */
+int reft_plan_staged_work(reft_plan *plan, uint64_t *gather_launches, uint64_t *copies);
 
 /* ---- S1 + S2 + S3: bucketed snapshot of one shard into pinned host memory -----------------------
  * Bucket by bucket, in order, the shard's stream is moved from the ragged span tensors to
@@ -145,7 +162,9 @@ int reft_snapshot_pack_range(reft_plan *plan, const void *const *span_ptrs,
                              uint64_t bucket_begin, uint64_t bucket_end,
                              reft_stream pack_stream, reft_stream copy_stream);
 int reft_plan_bucket_of(const reft_plan *plan, uint64_t offset, uint64_t *bucket);
-/* Block until the most recent reft_snapshot_pack on this plan has fully landed on the host. */
+/* Block until every reft_snapshot_pack[_range] issued on this plan so far has fully landed on the
+ * host (a call that ends on another stream than the one before it chains its completion behind
+ * that call's, on the device). */
 int reft_snapshot_wait(reft_plan *plan);
 /* 1 if it has landed (or none was issued), 0 if still in flight, negative on error. */
 int reft_snapshot_query(reft_plan *plan);
@@ -163,8 +182,13 @@ int reft_snapshot_query(reft_plan *plan);
  *                     the COMPLETED mark of section 4.4;
  *   reft_ckpt_latest  returns the newest buffer whose flag equals the generation begun in it
  *                     (*host_src == NULL, generation 0 if there is none yet).  Never blocks.
- * Errors: REFT_EINVAL (null arguments, commit without begin), REFT_ESIZE (cap < L), REFT_EHIP.
- * Not thread-safe; one snapshot in progress per reft_ckpt.
+ *   reft_ckpt_wait    blocks until every commit queued so far has landed.
+ * One snapshot at a time: reft_ckpt_begin returns REFT_EBUSY while a commit queued earlier has not
+ * landed (until then its buffer is neither complete nor free, and the other buffer holds the only
+ * complete copy).  A snapshot that was begun and never committed (torn) may be begun again once the
+ * caller has synchronised the streams it was issued on.  reft_ckpt_destroy waits for queued commits.
+ * Errors: REFT_EINVAL (null arguments, commit without begin), REFT_ESIZE (cap < L), REFT_EBUSY,
+ * REFT_EHIP.  Not thread-safe.
  */
 typedef struct reft_ckpt reft_ckpt;
 int reft_ckpt_create(reft_plan *plan, void *host_buf0, void *host_buf1, uint64_t cap,
@@ -173,6 +197,7 @@ void reft_ckpt_destroy(reft_ckpt *ckpt);
 int reft_ckpt_begin(reft_ckpt *ckpt, void **host_dst, uint64_t *generation);
 int reft_ckpt_commit(reft_ckpt *ckpt, reft_stream stream);
 int reft_ckpt_latest(reft_ckpt *ckpt, const void **host_src, uint64_t *generation);
+int reft_ckpt_wait(reft_ckpt *ckpt);
 
 /* ---- S1 alone / S7 alone: the gather and scatter kernels between device buffers ------------------
  * reft_pack_device:   dst_dev[0..L) = stream of the spans           (one launch over [0, L)).
@@ -200,8 +225,7 @@ int reft_parity_encode(reft_plan *plan, const void *const *shard_span_ptrs, uint
 /* ---- S6: decode the single lost shard (section 4.2, Eq. 2) ---------------------------------------
  * out_dev[i] = parity[i] ^ (XOR over the surviving shards s of shards[s][i]), i in [0, L).
  *
- * (The first call on a device allocates 18 KiB of device memory for the XOR kernel's counters
- * and keeps it until the process ends.)
+ * (The XOR kernel's counters live in 18 KiB of static device memory of the library.)
  *
  * shards[k]   host array of device pointers to the packed streams (L bytes each) of the node's k
  *             shards; exactly one entry is NULL: the lost shard.
@@ -321,7 +345,15 @@ int reft_restore_wait(reft_plan *plan);
  *                  such a plan answers the reft_plan_* queries and is refused (REFT_EINVAL) by
  *                  every call that would touch the GPU.
  * reft_set_tunable returns REFT_EINVAL for an unknown name or a value out of range.
+ *
+ * reft_plan_burst_stats (a diagnostic; waits for the device): how the writer waves of the plan's
+ * most recent write-burst launch spent their rounds, summed over the workgroups: stats[0] rounds
+ * in which the chip-wide meeting was seen complete, stats[1] rounds in which the polls ran out,
+ * stats[2] rounds without waiting (back-off after a time-out), stats[3] group completions counted
+ * by the meeting counter.  All zero if the plan has launched no burst kernel (or "burst_max_polls"
+ * is 0).
  */
+int reft_plan_burst_stats(reft_plan *plan, uint64_t stats[4]);
 int reft_set_tunable(const char *name, uint64_t value);
 int reft_get_tunable(const char *name, uint64_t *value);
 const char *reft_last_error(void);   /* thread-local, never NULL */

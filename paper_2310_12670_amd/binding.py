@@ -21,14 +21,15 @@ __all__ = [
     "reft_plan_tile_first_span",
     "reft_snapshot_pack", "reft_snapshot_pack_range", "reft_plan_bucket_of", "reft_snapshot_wait",
     "reft_snapshot_query", "reft_ckpt_create", "reft_ckpt_destroy", "reft_ckpt_begin",
-    "reft_ckpt_commit", "reft_ckpt_latest",
+    "reft_ckpt_commit", "reft_ckpt_latest", "reft_ckpt_wait", "REFT_EBUSY",
+    "reft_plan_staged_work", "reft_plan_burst_stats",
     "reft_pack_device", "reft_unpack_device", "reft_parity_encode", "reft_reconstruct",
     "reft_reconstruct_spans", "reft_segment_bytes", "reft_parity_encode_rotated",
     "reft_reconstruct_rotated", "reft_restore", "reft_restore_wait",
     "reft_set_tunable", "reft_get_tunable", "reft_last_error", "reft_version",
 ]
 
-REFT_OK, REFT_EINVAL, REFT_ESIZE, REFT_EHIP, REFT_EUNRECOVERABLE = 0, -1, -2, -3, -4
+REFT_OK, REFT_EINVAL, REFT_ESIZE, REFT_EHIP, REFT_EUNRECOVERABLE, REFT_EBUSY = 0, -1, -2, -3, -4, -5
 REFT_MAX_K = 32
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -84,6 +85,9 @@ def _load():
         "reft_pack_device": (i, [vp, vp, vp, u64, vp]),
         "reft_unpack_device": (i, [vp, vp, u64, vp, vp]),
         "reft_parity_encode": (i, [vp, vp, u32, vp, vp]),
+        "reft_plan_staged_work": (i, [vp, pu64, pu64]),
+        "reft_plan_burst_stats": (i, [vp, pu64]),
+        "reft_ckpt_wait": (i, [vp]),
         "reft_reconstruct": (i, [vp, u32, vp, u64, vp, ctypes.POINTER(u32), vp]),
         "reft_reconstruct_spans": (i, [vp, vp, u32, u32, vp, vp, vp]),
         "reft_segment_bytes": (u64, [vp, u32]),
@@ -275,6 +279,24 @@ def reft_ckpt_latest(ckpt):
     src, gen = ctypes.c_void_p(), ctypes.c_uint64()
     _check(_load().reft_ckpt_latest(ckpt, ctypes.byref(src), ctypes.byref(gen)))
     return src.value, gen.value
+
+
+def reft_ckpt_wait(ckpt) -> None:
+    _check(_load().reft_ckpt_wait(ckpt))
+
+
+def reft_plan_staged_work(plan):
+    """(gather kernel launches, copies) of a staged snapshot of the whole stream"""
+    a, b = ctypes.c_uint64(), ctypes.c_uint64()
+    _check(_load().reft_plan_staged_work(plan, ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
+
+
+def reft_plan_burst_stats(plan):
+    """(rounds met, rounds timed out, rounds not waited, group completions) of the last burst launch"""
+    v = (ctypes.c_uint64 * 4)()
+    _check(_load().reft_plan_burst_stats(plan, v))
+    return tuple(int(x) for x in v)
 
 
 def reft_snapshot_wait(plan) -> None:

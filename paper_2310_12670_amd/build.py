@@ -20,12 +20,12 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wal
          # per-kernel register counts, checked below
          "-Rpass-analysis=kernel-resource-usage"]
 
+HOST_PASS_NOTE = "'-packed-fp32-ops' is not a recognized feature for this target"
+
 # The write-burst kernels run two 5-wave workgroups per compute unit, all resident at once.  Measured
 # on gfx950: with more than 128 vector registers per lane only one such workgroup fits (four waves
 # of two workgroups can land on one SIMD: 4 x 128 = its 512 registers), the second half of the
 # grid then runs after the first, and the bursts lose their timing.
-HOST_PASS_NOTE = "'-packed-fp32-ops' is not a recognized feature for this target"
-
 BURST_KERNELS = ("k_gather_burst", "k_xor_contig_burst")
 BURST_MAX_VGPRS = 128
 

@@ -163,16 +163,59 @@ extern "C" const char *reft_version(void) { return "libreft 0.1 (gfx950)"; }
 // plan
 // ------------------------------------------------------------------------------------------------
 namespace {
-constexpr int kRing = 16;       // pointer-table uploads that may be in flight at once
+constexpr int kRing = 32;       // pointer tables the plan's cache holds at once
+constexpr int kUsers = 4;       // streams per cached table whose most recent use is tracked
+constexpr uint32_t kRingRows = 72;  // capacity of the cache, in rows of T pointers (>= 2 * (REFT_MAX_K + 1))
 constexpr int kMaxSlots = 64;   // staging slots used by the staged bucket pipelines
 constexpr int kGroups = 2;      // the slots form two groups that alternate (double buffering)
 constexpr uint32_t kCtrBlocks = 8;  // burst launches that may be in flight on one ring of counters
+constexpr size_t kPieceLists = 8;   // classified bucket ranges a plan remembers
 
 struct Event {
     hipEvent_t ev = nullptr;
     bool recorded = false;
 };
+
+struct Run {            // stream range [a, b) of consecutive small pieces: gather kernel + one copy
+    uint64_t a, b;
+};
+struct Dma {            // one piece (bucket x span) copied by the DMA path straight from its tensor
+    uint64_t o, n, span;
+};
+// How the bytes of a bucket range travel in the staged transport (see classify_pieces); depends
+// on the plan and two tunables only, so it is computed once and kept.
+struct PieceLists {
+    uint64_t b0 = 0, b1 = 0, dma_min = 0, gather_min = 0, tick = 0;
+    std::vector<Run> runs;
+    std::vector<Dma> dmas;
+};
+
+// One cached pointer table: `len` pointers at position `pos` of the plan's pool (pinned host
+// mirror and device copy).  `uploaded` is recorded behind the host-to-device copy; used[i] behind
+// the last kernel that read the table on stream user[i].
+struct PtrEntry {
+    bool live = false;
+    uint64_t pos = 0, len = 0, hash = 0, tick = 0;
+    hipStream_t up_stream = nullptr;
+    Event uploaded;
+    hipStream_t user[kUsers] = {};
+    Event used[kUsers];
+};
+
+// A plan derived from a base plan for the rotated placement, with the recipe that turns the
+// caller's pointers into its rows: entry (w * T' + t) says where piece t of window w starts.
+struct RowRecipe {
+    uint32_t span;      // span of the base plan, or kContig / kZeros
+    uint64_t add;       // byte offset inside that span (or inside the contiguous operand)
+};
+constexpr uint32_t kContig = 0xffffffffu, kZeros = 0xfffffffeu;
 }  // namespace
+
+struct DerivedPlan {
+    reft_plan *plan = nullptr;
+    uint32_t nwin = 0;
+    std::vector<RowRecipe> recipe;
+};
 
 struct reft_plan {
     bool host_only = false;           // sizing only: no device tables, data calls are refused
@@ -186,32 +229,39 @@ struct reft_plan {
     std::vector<uint32_t> first;      // [ntiles] host copy of the tile table
     uint64_t *d_off = nullptr;
     uint32_t *d_first = nullptr;
-    // ring of pointer tables: pinned host mirror and device copy, ring_rows rows of T per entry
-    uint32_t ring_rows = 0;
+    // cache of pointer tables: a pool of ring_cap pointers (pinned host mirror and device copy)
+    // handed out front to back, and the tables that currently live in it
+    uint64_t ring_cap = 0, ring_head = 0, ring_tick = 0;
     uint64_t *h_ptr = nullptr;
     uint64_t *d_ptr = nullptr;
-    Event ring_ev[kRing];
-    uint32_t ring_len[kRing] = {};    // pointers held by entry e (0 = empty)
-    uint64_t ring_used[kRing] = {};   // tick of the entry's last use (least recently used goes first)
-    uint32_t ring_hits[kRing] = {};   // reuses since the entry was uploaded
-    uint64_t ring_tick = 0;
+    PtrEntry ring[kRing];
+    // host scratch for the row tables of the XOR entry points ((REFT_MAX_K + 1) * T pointers)
+    std::vector<const void *> row_buf;
+    // classified piece lists of recent bucket ranges (the whole stream's is made at creation)
+    std::vector<PieceLists> pieces;
+    uint64_t pieces_tick = 0;
+    // stream on which the most recent snapshot's completion event was recorded
+    hipStream_t last_pack_stream = nullptr;
+    // ring of burst counter blocks in static device memory, shared by all plans of the GPU
+    uint32_t *static_ctr = nullptr;
     // bucket pipelines
     Event pack_filled[kGroups], pack_free[kGroups], pack_done, pack_begin, rest_begin;
     Event rest_filled[kGroups], rest_free[kGroups], rest_done, rest_copied;
-    // helper stream for the staged transport's piece copies (tunable "dma_streams"), created on
-    // first use at the default priority, and the events that fork it from / join it to copy_stream
+    // helper stream for the staged transport's piece copies (tunable "dma_streams"), created with
+    // the plan at the default priority, and the events that fork it from / join it to copy_stream
     hipStream_t aux = nullptr;
     Event aux_fork, aux_join;
     // rotated parity placement: plans derived from this one (merged piece lists of shifted
     // windows), keyed by (kind, k, member, segment), and a small all-zero device buffer that
     // stands in for the zero extension of the last segment
-    std::map<uint64_t, reft_plan *> derived;
+    std::map<uint64_t, DerivedPlan> derived;
     void *zeros = nullptr;
     // the piece copies of recent snapshot / restore calls as instantiated graphs (see copy_graph)
     struct CopyGraph {
         std::vector<uint64_t> key;
         hipGraphExec_t exec = nullptr;
         uint64_t used = 0;
+        hipEvent_t done = nullptr;    // recorded behind the most recent launch
     };
     std::vector<CopyGraph> graphs;
     uint64_t graph_tick = 0;
@@ -273,68 +323,163 @@ static int wait_on(hipStream_t s, const Event &e)
     return REFT_OK;
 }
 
+// ------------------------------------------------------------------------------------------------
+// static device memory of the library
+// ------------------------------------------------------------------------------------------------
+// `static_ctr` is the ring of burst counter blocks of reft_reconstruct, which has no plan to keep
+// them in.  In host code the name is a stand-in, not a device address: the address comes from
+// hipGetSymbolAddress, once per device.
+static __device__ __align__(256) uint32_t static_ctr[kCtrBlocks * (kBurstCtrBytes / sizeof(uint32_t))];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct DeviceStatics {
+    bool known = false;
+    uint32_t *ctr = nullptr;
+    int num_cus = 256;
+};
+std::mutex g_statics_mu;
+DeviceStatics g_statics[kMaxDevices];
+}  // namespace
+
+// The addresses of the static arrays on the current device (resolved on first use per device).
+static int device_statics(const DeviceStatics **out)
+{
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(REFT_EINVAL, "GPU %d: unsupported device index", dev);
+    std::lock_guard<std::mutex> lock(g_statics_mu);
+    DeviceStatics &d = g_statics[dev];
+    if (!d.known) {
+        void *b = nullptr;
+        HIPCHK(hipGetSymbolAddress(&b, HIP_SYMBOL(static_ctr)));
+        if (!b) return fail(REFT_EHIP, "hipGetSymbolAddress returned a null address");
+        hipDeviceProp_t prop;
+        HIPCHK(hipGetDeviceProperties(&prop, dev));
+        d.ctr = (uint32_t *)b;
+        d.num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        d.known = true;
+    }
+    *out = &d;
+    return REFT_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// cache of pointer tables
+// ------------------------------------------------------------------------------------------------
 static void free_ring(reft_plan *p)
 {
     if (p->h_ptr) (void)hipHostFree(p->h_ptr);
     if (p->d_ptr) (void)hipFree(p->d_ptr);
     p->h_ptr = nullptr;
     p->d_ptr = nullptr;
-    p->ring_rows = 0;
+    p->ring_cap = 0;
 }
 
-// Make room for pointer tables of `rows` rows.  Growing waits for earlier uploads to be consumed.
-static int ensure_ring(reft_plan *p, uint32_t rows)
+static uint64_t hash_ptrs(const void *const *ptrs, size_t n)
 {
-    if (rows <= p->ring_rows) return REFT_OK;
-    for (int i = 0; i < kRing; ++i)
-        if (p->ring_ev[i].recorded) HIPCHK(hipEventSynchronize(p->ring_ev[i].ev));
-    free_ring(p);
-    for (int i = 0; i < kRing; ++i) p->ring_len[i] = 0;
-    const size_t bytes = (size_t)kRing * rows * p->T * sizeof(uint64_t);
-    HIPCHK(hipHostMalloc((void **)&p->h_ptr, bytes, hipHostMallocDefault));
-    HIPCHK(hipMalloc((void **)&p->d_ptr, bytes));
-    p->ring_rows = rows;
+    uint64_t h = 0x9e3779b97f4a7c15ull ^ n;
+    for (size_t i = 0; i < n; ++i) {
+        h ^= (uint64_t)(uintptr_t)ptrs[i];
+        h *= 0x100000001b3ull;
+        h ^= h >> 29;
+    }
+    return h;
+}
+
+// The host waits for exactly the work that may still read the entry's table (its upload and the
+// kernels behind which a use was recorded): never for the whole device.
+static int retire_entry(PtrEntry &e)
+{
+    if (e.uploaded.recorded) HIPCHK(hipEventSynchronize(e.uploaded.ev));
+    e.uploaded.recorded = false;
+    for (int i = 0; i < kUsers; ++i) {
+        if (e.used[i].recorded) HIPCHK(hipEventSynchronize(e.used[i].ev));
+        e.used[i].recorded = false;
+        e.user[i] = nullptr;
+    }
+    e.live = false;
     return REFT_OK;
 }
 
-// Make `rows` x T pointers available on the device: reuse the ring entry that already holds exactly
-// these pointers (a trainer passes the same tensors every iteration), else overwrite the least
-// recently used entry and start its upload on `s`.  On success *dev_tab is the device table and
-// *entry the ring index, whose event the caller records after the last kernel that reads it.
+// Make `rows` x T pointers available on the device: reuse the cached table that already holds
+// exactly these pointers (a trainer passes the same tensors every iteration; a stream other than
+// the one that uploaded it waits for the upload only), else take the next room in the pool,
+// retiring the tables that lie there, and start the upload on `s`.  On success *dev_tab is the
+// device table and *entry the cache index to pass to release_ptrs after the last kernel that
+// reads the table.
 static int upload_ptrs(reft_plan *p, const void *const *ptrs, uint32_t rows, hipStream_t s,
                        const uint64_t **dev_tab, int *entry)
 {
-    int rc = ensure_ring(p, rows < 8 ? 8 : rows);
-    if (rc) return rc;
-    const size_t stride = (size_t)p->ring_rows * p->T;
-    const size_t n = (size_t)rows * p->T;
     static_assert(sizeof(void *) == sizeof(uint64_t), "pointers are 64-bit");
-    int e = -1;
-    for (int i = 0; i < kRing && e < 0; ++i)
-        if (p->ring_len[i] == n && !memcmp(p->h_ptr + i * stride, ptrs, n * sizeof(uint64_t))) e = i;
-    if (e < 0) {
-        e = 0;
-        for (int i = 1; i < kRing; ++i)
-            if (p->ring_used[i] < p->ring_used[e]) e = i;
-        // Nothing may still be reading the entry.  Its event covers the most recent use only, so
-        // an entry that was shared by several calls (possibly on different streams) is freed the
-        // safe way: wait for the whole device.  This is off the steady-state path (cache hits).
-        if (p->ring_hits[e]) HIPCHK(hipDeviceSynchronize());
-        else if (p->ring_ev[e].recorded) HIPCHK(hipEventSynchronize(p->ring_ev[e].ev));
-        uint64_t *h = p->h_ptr + e * stride;
-        memcpy(h, ptrs, n * sizeof(uint64_t));
-        p->ring_len[e] = (uint32_t)n;
-        p->ring_hits[e] = 0;
-        HIPCHK(hipMemcpyAsync(p->d_ptr + e * stride, h, n * sizeof(uint64_t), hipMemcpyHostToDevice,
-                              s));
-    } else {
-        // the table was uploaded on some stream earlier: this stream must see the upload
-        if (p->ring_ev[e].recorded) HIPCHK(hipStreamWaitEvent(s, p->ring_ev[e].ev, 0));
-        p->ring_hits[e] += 1;
+    const uint64_t n = (uint64_t)rows * p->T;
+    if (n > p->ring_cap)
+        return fail(REFT_ESIZE, "pointer table of %u rows exceeds the plan's cache (%llu pointers)",
+                    rows, (unsigned long long)p->ring_cap);
+    const uint64_t h = hash_ptrs(ptrs, n);
+    int rc;
+    for (int i = 0; i < kRing; ++i) {
+        PtrEntry &e = p->ring[i];
+        if (e.live && e.len == n && e.hash == h &&
+            !memcmp(p->h_ptr + e.pos, ptrs, n * sizeof(uint64_t))) {
+            if (e.up_stream != s && e.uploaded.recorded)
+                HIPCHK(hipStreamWaitEvent(s, e.uploaded.ev, 0));
+            e.tick = ++p->ring_tick;
+            *dev_tab = p->d_ptr + e.pos;
+            *entry = i;
+            return REFT_OK;
+        }
     }
-    p->ring_used[e] = ++p->ring_tick;
-    *dev_tab = p->d_ptr + e * stride;
-    *entry = e;
+    const uint64_t pos = p->ring_head + n > p->ring_cap ? 0 : p->ring_head;
+    int slot = -1;
+    for (int i = 0; i < kRing; ++i) {
+        PtrEntry &e = p->ring[i];
+        if (e.live && e.pos < pos + n && pos < e.pos + e.len && (rc = retire_entry(e))) return rc;
+        if (!e.live && slot < 0) slot = i;
+    }
+    if (slot < 0) {                                    // every slot is live: the oldest goes
+        slot = 0;
+        for (int i = 1; i < kRing; ++i)
+            if (p->ring[i].tick < p->ring[slot].tick) slot = i;
+        if ((rc = retire_entry(p->ring[slot]))) return rc;
+    }
+    PtrEntry &e = p->ring[slot];
+    memcpy(p->h_ptr + pos, ptrs, n * sizeof(uint64_t));
+    HIPCHK(hipMemcpyAsync(p->d_ptr + pos, p->h_ptr + pos, n * sizeof(uint64_t),
+                          hipMemcpyHostToDevice, s));
+    HIPCHK(hipEventRecord(e.uploaded.ev, s));
+    e.uploaded.recorded = true;
+    e.up_stream = s;
+    e.live = true;
+    e.pos = pos;
+    e.len = n;
+    e.hash = h;
+    e.tick = ++p->ring_tick;
+    p->ring_head = pos + n;
+    *dev_tab = p->d_ptr + pos;
+    *entry = slot;
+    return REFT_OK;
+}
+
+// Record, on stream s, that the kernels queued so far were the last ones to read entry's table.
+static int release_ptrs(reft_plan *p, int entry, hipStream_t s)
+{
+    PtrEntry &e = p->ring[entry];
+    int i = -1;
+    for (int u = 0; u < kUsers && i < 0; ++u)
+        if (e.used[u].recorded && e.user[u] == s) i = u;
+    for (int u = 0; u < kUsers && i < 0; ++u)
+        if (!e.used[u].recorded) i = u;
+    for (int u = 0; u < kUsers && i < 0; ++u)
+        if (hipEventQuery(e.used[u].ev) == hipSuccess) i = u;
+    if (i < 0) {                                       // more streams than tracked: wait for one
+        i = 0;
+        HIPCHK(hipEventSynchronize(e.used[0].ev));
+    }
+    (void)hipGetLastError();                           // hipEventQuery's "not ready" is no error
+    e.user[i] = s;
+    HIPCHK(hipEventRecord(e.used[i].ev, s));
+    e.used[i].recorded = true;
     return REFT_OK;
 }
 
@@ -363,6 +508,8 @@ static int check_span_ptrs(const reft_plan *p, const void *const *ptrs, uint32_t
                             (unsigned long long)(p->off[t + 1] - p->off[t]));
     return REFT_OK;
 }
+
+static const PieceLists &pieces_of(reft_plan *p, uint64_t b0, uint64_t b1);
 
 extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
                                 const uint64_t *bucket_nbytes, uint64_t NB,
@@ -454,8 +601,14 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
                      hipMemcpyHostToDevice));
     HIPCHK(hipMalloc((void **)&p->burst_ctr, kCtrBlocks * kBurstCtrBytes));
     int rc;
-    for (int i = 0; i < kRing; ++i)
-        if ((rc = make_event(p->ring_ev[i]))) return rc;
+    const DeviceStatics *ds = nullptr;
+    if ((rc = device_statics(&ds))) return rc;
+    p->static_ctr = ds->ctr;
+    for (int i = 0; i < kRing; ++i) {
+        if ((rc = make_event(p->ring[i].uploaded))) return rc;
+        for (int u = 0; u < kUsers; ++u)
+            if ((rc = make_event(p->ring[i].used[u]))) return rc;
+    }
     for (int i = 0; i < kGroups; ++i) {
         if ((rc = make_event(p->pack_filled[i])) || (rc = make_event(p->pack_free[i])) ||
             (rc = make_event(p->rest_filled[i])) || (rc = make_event(p->rest_free[i])))
@@ -466,7 +619,16 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
         (rc = make_event(p->rest_begin)) || (rc = make_event(p->aux_fork)) ||
         (rc = make_event(p->aux_join)))
         return rc;
-    if ((rc = ensure_ring(p, 8))) return rc;
+    // (a stream that never gets work occupies no hardware queue)
+    HIPCHK(hipStreamCreateWithFlags(&p->aux, hipStreamNonBlocking));
+    // everything a data-moving call needs is made here: the pointer-table pool, the host scratch
+    // for row tables, and the whole stream's piece lists for the staged transport
+    p->ring_cap = (uint64_t)kRingRows * T;
+    HIPCHK(hipHostMalloc((void **)&p->h_ptr, p->ring_cap * sizeof(uint64_t), hipHostMallocDefault));
+    HIPCHK(hipMalloc((void **)&p->d_ptr, p->ring_cap * sizeof(uint64_t)));
+    p->row_buf.resize((size_t)(REFT_MAX_K + 1) * T);
+    p->pieces.reserve(kPieceLists);
+    (void)pieces_of(p, 0, p->NB);
 
     guard.p = nullptr;
     *out = p;
@@ -485,7 +647,10 @@ extern "C" void reft_plan_destroy(reft_plan *p)
             e.ev = nullptr;
         }
     };
-    for (int i = 0; i < kRing; ++i) drain(p->ring_ev[i]);
+    for (int i = 0; i < kRing; ++i) {
+        drain(p->ring[i].uploaded);
+        for (int u = 0; u < kUsers; ++u) drain(p->ring[i].used[u]);
+    }
     for (int i = 0; i < kGroups; ++i) {
         drain(p->pack_filled[i]);
         drain(p->pack_free[i]);
@@ -501,10 +666,15 @@ extern "C" void reft_plan_destroy(reft_plan *p)
     drain(p->pack_begin);
     drain(p->rest_begin);
     free_ring(p);
-    for (auto &g : p->graphs)
+    for (auto &g : p->graphs) {
+        if (g.done) {
+            (void)hipEventSynchronize(g.done);
+            (void)hipEventDestroy(g.done);
+        }
         if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    }
     if (p->burst_ctr) (void)hipFree(p->burst_ctr);
-    for (auto &kv : p->derived) reft_plan_destroy(kv.second);
+    for (auto &kv : p->derived) reft_plan_destroy(kv.second.plan);
     p->derived.clear();
     if (p->zeros) (void)hipFree(p->zeros);
     if (p->d_off) (void)hipFree(p->d_off);
@@ -574,18 +744,38 @@ extern "C" int reft_plan_split(const reft_plan *p, double t_bubble, double t_ss,
     return REFT_OK;
 }
 
+extern "C" int reft_plan_staged_work(reft_plan *p, uint64_t *gather_launches, uint64_t *copies)
+{
+    REFT_GUARD_BEGIN
+    if (!p || !gather_launches || !copies)
+        return fail(REFT_EINVAL, "reft_plan_staged_work: null argument");
+    const PieceLists &pl = pieces_of(p, 0, p->NB);
+    *gather_launches = pl.runs.size();
+    *copies = pl.runs.size() + pl.dmas.size();
+    return REFT_OK;
+    REFT_GUARD_END("reft_plan_staged_work")
+}
+
+extern "C" int reft_plan_burst_stats(reft_plan *p, uint64_t stats[4])
+{
+    int rc = check_plan(p, "reft_plan_burst_stats");
+    if (rc) return rc;
+    if (!stats) return fail(REFT_EINVAL, "reft_plan_burst_stats: null argument");
+    stats[0] = stats[1] = stats[2] = stats[3] = 0;
+    if (p->burst_next == 0) return REFT_OK;              // no burst launch on this plan yet
+    const uint32_t slot = (p->burst_next - 1) % kCtrBlocks;
+    const uint32_t *blk = p->burst_ctr + (size_t)slot * (kBurstCtrBytes / sizeof(uint32_t));
+    uint32_t w[4] = {0, 0, 0, 0};
+    HIPCHK(hipDeviceSynchronize());                      // a diagnostic: the launch must have ended
+    HIPCHK(hipMemcpy(w, blk + kBurstDiagWord, 3 * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    HIPCHK(hipMemcpy(w + 3, blk + 8 * 64, sizeof(uint32_t), hipMemcpyDeviceToHost));
+    for (int i = 0; i < 4; ++i) stats[i] = w[i];
+    return REFT_OK;
+}
+
 // ------------------------------------------------------------------------------------------------
 // how the bytes of a bucket range travel between the tensors and the host (staged transport)
 // ------------------------------------------------------------------------------------------------
-namespace {
-struct Run {            // stream range [a, b) of consecutive small pieces: gather kernel + one copy
-    uint64_t a, b;
-};
-struct Dma {            // one piece (bucket x span) copied by the DMA path straight from its tensor
-    uint64_t o, n, span;
-};
-}  // namespace
-
 // A piece of at least dma_min bytes needs no kernel: the runtime's copy engines move it between
 // the tensor and the host buffer, which costs kernels running beside it next to nothing.  Smaller
 // pieces are worth a copy of their own only when few of them lie together; a run of at least
@@ -593,9 +783,9 @@ struct Dma {            // one piece (bucket x span) copied by the DMA path stra
 // kernel launch and leaves as one copy (many small tensors would otherwise mean thousands of tiny
 // transfers).
 static void classify_pieces(const reft_plan *p, uint64_t bucket_begin, uint64_t bucket_end,
-                            std::vector<Run> &runs, std::vector<Dma> &dmas)
+                            uint64_t dma_min, uint64_t gather_min, std::vector<Run> &runs,
+                            std::vector<Dma> &dmas)
 {
-    const uint64_t dma_min = g_dma_min.load(), gather_min = g_gather_min.load();
     std::vector<Dma> pending;
     auto flush = [&]() {
         if (pending.empty()) return;
@@ -631,6 +821,37 @@ static void classify_pieces(const reft_plan *p, uint64_t bucket_begin, uint64_t 
         }
         flush();                                         // a run never crosses a bucket
     }
+}
+
+// The piece lists of buckets [b0, b1) under the current tunables: made once per range and kept
+// (the least recently used of kPieceLists ranges goes when another one is asked for).
+static const PieceLists &pieces_of(reft_plan *p, uint64_t b0, uint64_t b1)
+{
+    const uint64_t dma_min = g_dma_min.load(), gather_min = g_gather_min.load();
+    for (auto &pl : p->pieces)
+        if (pl.b0 == b0 && pl.b1 == b1 && pl.dma_min == dma_min && pl.gather_min == gather_min) {
+            pl.tick = ++p->pieces_tick;
+            return pl;
+        }
+    PieceLists *pl = nullptr;
+    p->pieces.reserve(kPieceLists);                     // references handed out stay valid
+    if (p->pieces.size() < kPieceLists) {
+        p->pieces.emplace_back();
+        pl = &p->pieces.back();
+    } else {
+        pl = &p->pieces[0];
+        for (auto &q : p->pieces)
+            if (q.tick < pl->tick) pl = &q;
+        pl->runs.clear();
+        pl->dmas.clear();
+    }
+    pl->b0 = b0;
+    pl->b1 = b1;
+    pl->dma_min = dma_min;
+    pl->gather_min = gather_min;
+    pl->tick = ++p->pieces_tick;
+    classify_pieces(p, b0, b1, dma_min, gather_min, pl->runs, pl->dmas);
+    return *pl;
 }
 
 // The piece copies of a call as one hipGraph of memcpy nodes, launched on copy_stream.  A trainer
@@ -685,15 +906,19 @@ static int copy_graph(reft_plan *p, const std::vector<Dma> &dmas, hipStream_t cs
             size_t lru = 0;
             for (size_t i = 1; i < p->graphs.size(); ++i)
                 if (p->graphs[i].used < p->graphs[lru].used) lru = i;
-            HIPCHK(hipDeviceSynchronize());
+            HIPCHK(hipEventSynchronize(p->graphs[lru].done));
             (void)hipGraphExecDestroy(p->graphs[lru].exec);
+            (void)hipEventDestroy(p->graphs[lru].done);
             p->graphs.erase(p->graphs.begin() + (long)lru);
         }
-        p->graphs.push_back(reft_plan::CopyGraph{std::move(key), exec, 0});
+        hipEvent_t done = nullptr;
+        HIPCHK(hipEventCreateWithFlags(&done, hipEventDisableTiming));
+        p->graphs.push_back(reft_plan::CopyGraph{std::move(key), exec, 0, done});
         hit = &p->graphs.back();
     }
     hit->used = ++p->graph_tick;
     HIPCHK(hipGraphLaunch(hit->exec, cs));
+    HIPCHK(hipEventRecord(hit->done, cs));
     return REFT_OK;
 }
 
@@ -706,7 +931,6 @@ static int issue_piece_copies(reft_plan *p, const std::vector<Dma> &dmas, hipStr
     int rc;
     const bool two = g_dma_streams.load() == 2 && dmas.size() >= 4;
     if (two) {
-        if (!p->aux) HIPCHK(hipStreamCreateWithFlags(&p->aux, hipStreamNonBlocking));
         if ((rc = record(p->aux_fork, cs))) return rc;
         if ((rc = wait_on(p->aux, p->aux_fork))) return rc;
     }
@@ -721,6 +945,17 @@ static int issue_piece_copies(reft_plan *p, const std::vector<Dma> &dmas, hipStr
 // ------------------------------------------------------------------------------------------------
 // S1 + S2 + S3: snapshot
 // ------------------------------------------------------------------------------------------------
+// Record the snapshot completion event behind the call's last work.  The event covers every
+// snapshot call issued on the plan so far: when the previous call ended on another stream, this
+// one's completion also waits (on the device) for that call's.
+static int record_pack_done(reft_plan *p, hipStream_t s)
+{
+    int rc;
+    if (p->pack_done.recorded && p->last_pack_stream != s && (rc = wait_on(s, p->pack_done))) return rc;
+    p->last_pack_stream = s;
+    return record(p->pack_done, s);
+}
+
 static int staging_slots(const reft_plan *p, const void *staging, uint64_t staging_bytes,
                          const char *who, int *nslots)
 {
@@ -773,8 +1008,8 @@ extern "C" int reft_snapshot_pack_range(reft_plan *p, const void *const *span_pt
         for (uint64_t b = bucket_begin; b < bucket_end; ++b)
             HIPCHK(launch_gather(pt, tab, 1, false, nullptr, hview, p->bstart[b], p->bstart[b + 1],
                                  cfg, ps));
-        if ((rc = record(p->ring_ev[entry], ps))) return rc;
-        return record(p->pack_done, ps);
+        if ((rc = release_ptrs(p, entry, ps))) return rc;
+        return record_pack_done(p, ps);
     }
 
     // Staged transport.  Large pieces go by DMA straight from their tensors; runs of small pieces
@@ -783,9 +1018,9 @@ extern "C" int reft_snapshot_pack_range(reft_plan *p, const void *const *span_pt
     // (cross-stream events are costly when thousands are in flight).
     int nslots = 1;
     if ((rc = staging_slots(p, staging, staging_bytes, "reft_snapshot_pack", &nslots))) return rc;
-    std::vector<Run> runs;
-    std::vector<Dma> dmas;
-    classify_pieces(p, bucket_begin, bucket_end, runs, dmas);
+    const PieceLists &pl = pieces_of(p, bucket_begin, bucket_end);
+    const std::vector<Run> &runs = pl.runs;
+    const std::vector<Dma> &dmas = pl.dmas;
     const uint64_t stride = slot_stride(p);
     // The tensors are read on both streams.  The caller orders pack_stream behind whatever
     // produced them; copy_stream joins pack_stream here so the same ordering covers its copies.
@@ -823,7 +1058,7 @@ extern "C" int reft_snapshot_pack_range(reft_plan *p, const void *const *span_pt
             }
             if ((rc = record(p->pack_free[g], cs))) return rc;
         }
-        if ((rc = record(p->ring_ev[entry], ps))) return rc;
+        if ((rc = release_ptrs(p, entry, ps))) return rc;
     }
     const uint64_t gmode = g_graph_copies.load();
     if (gmode && g_dma_streams.load() == 1 && dmas.size() >= 8) {
@@ -835,7 +1070,7 @@ extern "C" int reft_snapshot_pack_range(reft_plan *p, const void *const *span_pt
                })))
         return rc;
     // completion: every copy above is on copy_stream, the gathered ones behind their kernels
-    return record(p->pack_done, cs);
+    return record_pack_done(p, cs);
     REFT_GUARD_END("reft_snapshot_pack")
 }
 
@@ -893,7 +1128,24 @@ struct reft_ckpt {
     uint64_t begun[2] = {0, 0};      // generation most recently started in buf[i] (host side)
     uint64_t generation = 0;
     int ongoing = -1;                // buffer of the snapshot in progress, -1 if none
+    Event committed_ev[2];           // recorded behind the commit kernel of buf[i]
 };
+
+// 1 if a commit has been queued into buffer i and has not landed yet, 0 if not, negative on error.
+static int commit_pending(reft_ckpt *c, int i)
+{
+    if (!c->committed_ev[i].recorded) return 0;
+    const hipError_t e = hipEventQuery(c->committed_ev[i].ev);
+    if (e == hipSuccess) {
+        c->committed_ev[i].recorded = false;
+        return 0;
+    }
+    if (e == hipErrorNotReady) {
+        (void)hipGetLastError();
+        return 1;
+    }
+    return fail(REFT_EHIP, "hipEventQuery failed: %s", hipGetErrorString(e));
+}
 
 __global__ void k_commit(uint64_t *slot, uint64_t generation)
 {
@@ -924,6 +1176,11 @@ extern "C" int reft_ckpt_create(reft_plan *p, void *host_buf0, void *host_buf1, 
         return fail(REFT_EHIP, "hipHostMalloc failed: %s", hipGetErrorString(e));
     }
     c->committed[0] = c->committed[1] = 0;
+    for (int i = 0; i < 2; ++i)
+        if ((rc = make_event(c->committed_ev[i]))) {
+            reft_ckpt_destroy(c);
+            return rc;
+        }
     *out = c;
     return REFT_OK;
 }
@@ -931,8 +1188,25 @@ extern "C" int reft_ckpt_create(reft_plan *p, void *host_buf0, void *host_buf1, 
 extern "C" void reft_ckpt_destroy(reft_ckpt *c)
 {
     if (!c) return;
+    // a commit kernel that is still queued stores into the flags: let it finish first
+    for (int i = 0; i < 2; ++i)
+        if (c->committed_ev[i].ev) {
+            if (c->committed_ev[i].recorded) (void)hipEventSynchronize(c->committed_ev[i].ev);
+            (void)hipEventDestroy(c->committed_ev[i].ev);
+        }
     if (c->committed) (void)hipHostFree(c->committed);
     delete c;
+}
+
+extern "C" int reft_ckpt_wait(reft_ckpt *c)
+{
+    if (!c) return fail(REFT_EINVAL, "reft_ckpt_wait: null argument");
+    for (int i = 0; i < 2; ++i)
+        if (c->committed_ev[i].recorded) {
+            HIPCHK(hipEventSynchronize(c->committed_ev[i].ev));
+            c->committed_ev[i].recorded = false;
+        }
+    return REFT_OK;
 }
 
 static uint64_t committed_of(const reft_ckpt *c, int i)
@@ -959,6 +1233,16 @@ static int latest_complete(const reft_ckpt *c, uint64_t *gen)
 extern "C" int reft_ckpt_begin(reft_ckpt *c, void **host_dst, uint64_t *generation)
 {
     if (!c || !host_dst) return fail(REFT_EINVAL, "reft_ckpt_begin: null argument");
+    // While a commit is in flight its buffer is neither complete nor free, and overwriting the
+    // other one would leave no complete snapshot should that commit never land.
+    for (int i = 0; i < 2; ++i) {
+        const int pend = commit_pending(c, i);
+        if (pend < 0) return pend;
+        if (pend)
+            return fail(REFT_EBUSY, "reft_ckpt_begin: the commit of generation %llu has not landed "
+                                    "yet (reft_ckpt_wait blocks until it has)",
+                        (unsigned long long)c->begun[i]);
+    }
     // write into the buffer that does not hold the newest complete snapshot
     const int keep = latest_complete(c, nullptr);
     const int i = keep == 0 ? 1 : 0;
@@ -979,6 +1263,7 @@ extern "C" int reft_ckpt_commit(reft_ckpt *c, reft_stream stream)
     hipLaunchKernelGGL(k_commit, dim3(1), dim3(1), 0, (hipStream_t)stream,
                        c->committed + c->ongoing, c->begun[c->ongoing]);
     HIPCHK(hipGetLastError());
+    if ((rc = record(c->committed_ev[c->ongoing], (hipStream_t)stream))) return rc;
     c->ongoing = -1;
     return REFT_OK;
 }
@@ -1011,7 +1296,7 @@ extern "C" int reft_pack_device(reft_plan *p, const void *const *span_ptrs, void
     if ((rc = upload_ptrs(p, span_ptrs, 1, s, &tab, &entry))) return rc;
     HIPCHK(launch_gather(p->tables(), tab, 1, false, nullptr, (uint64_t)(uintptr_t)dst_dev, 0, p->L,
                          launch_cfg(p), s));
-    return record(p->ring_ev[entry], s);
+    return release_ptrs(p, entry, s);
 }
 
 extern "C" int reft_unpack_device(reft_plan *p, const void *src_dev, uint64_t src_bytes,
@@ -1031,7 +1316,7 @@ extern "C" int reft_unpack_device(reft_plan *p, const void *src_dev, uint64_t sr
     if ((rc = upload_ptrs(p, span_ptrs, 1, s, &tab, &entry))) return rc;
     HIPCHK(launch_scatter(p->tables(), tab, (uint64_t)(uintptr_t)src_dev, 0, p->L, launch_cfg(p),
                           s));
-    return record(p->ring_ev[entry], s);
+    return release_ptrs(p, entry, s);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1040,7 +1325,7 @@ extern "C" int reft_unpack_device(reft_plan *p, const void *src_dev, uint64_t sr
 static BurstCfg burst_cfg(uint32_t *ring, uint32_t slot, int num_cus)
 {
     BurstCfg bc;
-    bc.ctr = ring + (size_t)(slot % kCtrBlocks) * (kBurstCtrBytes / sizeof(uint32_t));
+    bc.ctr = ring + (size_t)slot * (kBurstCtrBytes / sizeof(uint32_t));
     bc.stage_bytes = (uint32_t)g_burst_stage.load();
     bc.wgs_per_cu = (uint32_t)g_burst_wgs.load();
     bc.num_cus = (uint32_t)num_cus;
@@ -1057,25 +1342,15 @@ static uint64_t dense_tiles(const reft_plan *p, uint32_t small_pieces)
 }
 
 
-// XOR of `nrows` rows of span pointers (row stride T of plan p) into a contiguous destination or,
-// if dst_row is given, into the destination's own spans.  More than kMaxSrc rows are folded in
-// passes.  rows (and dst_row) are host arrays; they are uploaded as one table.
-static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const void *const *dst_row,
-                    void *dst_contig, hipStream_t s)
+// The XOR passes over a device table of `nrows` rows of span pointers (row stride T of plan p)
+// into a contiguous destination or, if dtab is given, into the destination's own spans (dst_row
+// is the host copy of that row, used to decide which kernel applies).  More than kMaxSrc rows
+// are folded in passes.  ctr_ring holds ctr_blocks blocks of burst counters; *ctr_next picks one.
+static int xor_passes(reft_plan *p, const uint64_t *tab, uint32_t nrows, const uint64_t *dtab,
+                      const void *const *dst_row, void *dst_contig, uint32_t *ctr_ring,
+                      uint32_t ctr_blocks, uint32_t *ctr_next, hipStream_t s)
 {
-    int rc;
     const uint64_t T = p->T;
-    const uint64_t *tab = nullptr;
-    int entry = 0;
-    if (dst_row) {
-        std::vector<const void *> all((size_t)(nrows + 1) * T);
-        std::copy(rows, rows + (size_t)nrows * T, all.begin());
-        std::copy(dst_row, dst_row + T, all.begin() + (size_t)nrows * T);
-        if ((rc = upload_ptrs(p, all.data(), nrows + 1, s, &tab, &entry))) return rc;
-    } else {
-        if ((rc = upload_ptrs(p, rows, nrows, s, &tab, &entry))) return rc;
-    }
-    const uint64_t *dtab = dst_row ? tab + (uint64_t)nrows * T : nullptr;
     const LaunchCfg cfg = launch_cfg(p);
     const PlanTables pt = p->tables();
     // Passes over many rows separate reads and writes in time with the burst kernel.  It walks a
@@ -1102,7 +1377,7 @@ static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const
         const uint32_t cap = (uint32_t)kMaxSrc - (acc ? 1u : 0u);
         if (n > cap) n = cap;
         if (burst_ok && n + (acc ? 1u : 0u) >= g_burst_min_rows.load()) {
-            const BurstCfg bc = burst_cfg(p->burst_ctr, p->burst_next++, p->num_cus);
+            BurstCfg bc = burst_cfg(ctr_ring, (*ctr_next)++ % ctr_blocks, p->num_cus);
             HIPCHK(launch_gather_burst(pt, tab + (uint64_t)done * T, (int)n, acc, dtab, vb, 0, p->L,
                                        cfg, bc, s));
         } else {
@@ -1111,7 +1386,33 @@ static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const
         }
         done += n;
     }
-    return record(p->ring_ev[entry], s);
+    return REFT_OK;
+}
+
+// XOR of `nrows` host rows of span pointers into a contiguous destination or, if dst_row is
+// given, into the destination's own spans.  The rows are uploaded as one table through the
+// plan's cache (rows and dst_row may lie in the plan's row_buf).
+static int xor_rows(reft_plan *p, const void *const *rows, uint32_t nrows, const void *const *dst_row,
+                    void *dst_contig, hipStream_t s)
+{
+    int rc;
+    const uint64_t T = p->T;
+    const uint64_t *tab = nullptr;
+    int entry = 0;
+    if (dst_row) {
+        // one table: the source rows, then the destination row
+        const void **all = p->row_buf.data();
+        if (rows != all) std::copy(rows, rows + (size_t)nrows * T, all);
+        if (dst_row != all + (size_t)nrows * T) std::copy(dst_row, dst_row + T, all + (size_t)nrows * T);
+        if ((rc = upload_ptrs(p, all, nrows + 1, s, &tab, &entry))) return rc;
+    } else {
+        if ((rc = upload_ptrs(p, rows, nrows, s, &tab, &entry))) return rc;
+    }
+    const uint64_t *dtab = dst_row ? tab + (uint64_t)nrows * T : nullptr;
+    if ((rc = xor_passes(p, tab, nrows, dtab, dst_row, dst_contig, p->burst_ctr, kCtrBlocks,
+                         &p->burst_next, s)))
+        return rc;
+    return release_ptrs(p, entry, s);
 }
 
 extern "C" int reft_parity_encode(reft_plan *p, const void *const *shard_span_ptrs, uint32_t k,
@@ -1133,12 +1434,11 @@ extern "C" int reft_parity_encode(reft_plan *p, const void *const *shard_span_pt
 // rotated placement of the parity (section 4.2): every member protects one segment of every other
 // ------------------------------------------------------------------------------------------------
 namespace {
-// One operand of a rotated XOR: `len` bytes starting at stream offset w of a shard (bytes at or
-// beyond L read as zero), or a contiguous buffer (span_ptrs == nullptr).
-struct Window {
-    const void *const *span_ptrs;   // T span pointers of the shard, or nullptr
-    const void *contig;             // base of a contiguous operand (window offset 0)
-    uint64_t w;                     // stream offset of the window's first byte
+// One operand of a rotated XOR: the bytes at stream offsets [w, w + len) of a shard (bytes at or
+// beyond L read as zero), or a contiguous buffer of len bytes.
+struct WinSpec {
+    bool contig;
+    uint64_t w;
 };
 }  // namespace
 
@@ -1149,19 +1449,33 @@ extern "C" uint64_t reft_segment_bytes(const reft_plan *p, uint32_t k)
     return (!p || k < 2) ? 0 : (p->L + (k - 2)) / (k - 1);
 }
 
-// The plan whose spans are the merged pieces of windows of `len` bytes at the given stream
-// offsets of the base plan (every span boundary of every window becomes a boundary).
-static int derived_plan(reft_plan *p, uint64_t key, const std::vector<uint64_t> &offsets,
-                        uint64_t len, reft_plan **out)
+static int ensure_zeros(reft_plan *p)
+{
+    if (p->zeros) return REFT_OK;
+    HIPCHK(hipMalloc(&p->zeros, 256));
+    HIPCHK(hipMemset(p->zeros, 0, 256));
+    return REFT_OK;
+}
+
+// The plan whose spans are the merged pieces of `nwin` windows of `len` bytes of the base plan
+// (every span boundary of every window becomes a boundary), with the recipe that turns the
+// caller's pointers into its rows.  Built on first use and kept in the base plan.
+static int derived_plan(reft_plan *p, uint64_t key, const WinSpec *wins, uint32_t nwin, uint64_t len,
+                        const DerivedPlan **out)
 {
     auto it = p->derived.find(key);
     if (it != p->derived.end()) {
-        *out = it->second;
+        *out = &it->second;
         return REFT_OK;
     }
+    int rc = ensure_zeros(p);
+    if (rc) return rc;
     std::vector<uint64_t> cuts{0, len};
-    for (uint64_t w : offsets) {
-        // span starts strictly inside (w, w + len)
+    for (uint32_t q = 0; q < nwin; ++q) {
+        if (wins[q].contig) continue;
+        const uint64_t w = wins[q].w;
+        // span starts strictly inside (w, w + len); off[T] = L makes the end of the stream a
+        // boundary too, so the zero extension of the last segment starts on a piece boundary
         auto lo = std::upper_bound(p->off.begin(), p->off.end(), w);
         for (; lo != p->off.end() && *lo < w + len; ++lo) cuts.push_back(*lo - w);
     }
@@ -1169,44 +1483,56 @@ static int derived_plan(reft_plan *p, uint64_t key, const std::vector<uint64_t> 
     cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
     std::vector<uint64_t> sizes(cuts.size() - 1);
     for (size_t i = 0; i + 1 < cuts.size(); ++i) sizes[i] = cuts[i + 1] - cuts[i];
-    reft_plan *d = nullptr;
-    int rc = reft_plan_create(sizes.data(), sizes.size(), nullptr, 0, 0, &d);
-    if (rc) return rc;
-    p->derived[key] = d;
-    *out = d;
+    DerivedPlan dp;
+    if ((rc = reft_plan_create(sizes.data(), sizes.size(), nullptr, 0, 0, &dp.plan))) return rc;
+    struct Guard {
+        reft_plan *d;
+        ~Guard() { if (d) reft_plan_destroy(d); }
+    } guard{dp.plan};
+    const reft_plan *d = dp.plan;
+    dp.nwin = nwin;
+    dp.recipe.resize((size_t)nwin * d->T);
+    for (uint32_t q = 0; q < nwin; ++q)
+        for (uint64_t t = 0; t < d->T; ++t) {
+            RowRecipe &r = dp.recipe[(size_t)q * d->T + t];
+            const uint64_t x = d->off[t];
+            if (wins[q].contig) {
+                r = RowRecipe{kContig, x};
+                continue;
+            }
+            const uint64_t y = wins[q].w + x;
+            if (y >= p->L) {                       // zero extension of the last segment
+                if (d->off[t + 1] - x > 256) return fail(REFT_EINVAL, "internal: zero pad too long");
+                r = RowRecipe{kZeros, 0};
+                continue;
+            }
+            const uint64_t sp = (uint64_t)(std::upper_bound(p->off.begin(), p->off.end(), y) -
+                                           p->off.begin()) - 1;        // off[sp] <= y < off[sp + 1]
+            r = RowRecipe{(uint32_t)sp, y - p->off[sp]};
+        }
+    guard.d = nullptr;
+    auto ins = p->derived.emplace(key, std::move(dp));
+    *out = &ins.first->second;
     return REFT_OK;
 }
 
-// Row of span pointers of derived plan d for one window.
-static int window_row(reft_plan *p, const reft_plan *d, const Window &win, const void **row)
+// Row q of the derived plan's pointer table from the operand's own pointers.
+static int window_row(const reft_plan *p, const DerivedPlan &dp, uint32_t q,
+                      const void *const *span_ptrs, const void *contig, const void **row)
 {
-    for (uint64_t t = 0; t < d->T; ++t) {
-        const uint64_t x = d->off[t];
-        if (!win.span_ptrs) {
-            row[t] = (const uint8_t *)win.contig + x;
-            continue;
-        }
-        const uint64_t y = win.w + x;
-        if (y >= p->L) {                       // zero extension of the last segment
-            if (d->off[t + 1] - x > 256) return fail(REFT_EINVAL, "internal: zero pad too long");
+    const uint64_t Td = dp.plan->T;
+    const RowRecipe *rec = dp.recipe.data() + (size_t)q * Td;
+    for (uint64_t t = 0; t < Td; ++t) {
+        if (rec[t].span == kContig) {
+            row[t] = (const uint8_t *)contig + rec[t].add;
+        } else if (rec[t].span == kZeros) {
             row[t] = p->zeros;
-            continue;
+        } else {
+            if (!span_ptrs[rec[t].span])
+                return fail(REFT_EINVAL, "rotated parity: span %u is null but has bytes", rec[t].span);
+            row[t] = (const uint8_t *)span_ptrs[rec[t].span] + rec[t].add;
         }
-        const uint64_t sp = (uint64_t)(std::upper_bound(p->off.begin(), p->off.end(), y) -
-                                       p->off.begin()) - 1;        // off[sp] <= y < off[sp + 1]
-        if (!win.span_ptrs[sp])
-            return fail(REFT_EINVAL, "rotated parity: span %llu is null but has bytes",
-                        (unsigned long long)sp);
-        row[t] = (const uint8_t *)win.span_ptrs[sp] + (y - p->off[sp]);
     }
-    return REFT_OK;
-}
-
-static int ensure_zeros(reft_plan *p)
-{
-    if (p->zeros) return REFT_OK;
-    HIPCHK(hipMalloc(&p->zeros, 256));
-    HIPCHK(hipMemset(p->zeros, 0, 256));
     return REFT_OK;
 }
 
@@ -1225,24 +1551,24 @@ extern "C" int reft_parity_encode_rotated(reft_plan *p, const void *const *shard
     const uint64_t Lseg = reft_segment_bytes(p, k);
     if (Lseg == 0) return REFT_OK;
     if (!parity_dev) return fail(REFT_EINVAL, "reft_parity_encode_rotated: null parity buffer");
-    if ((rc = ensure_zeros(p))) return rc;
-    std::vector<Window> wins;
-    std::vector<uint64_t> offsets;
+    WinSpec wins[REFT_MAX_K];
+    uint32_t shard_of[REFT_MAX_K];
+    uint32_t nwin = 0;
     for (uint32_t j = 0; j < k; ++j) {
         if (j == member) continue;
-        wins.push_back(Window{shard_span_ptrs + (size_t)j * p->T, nullptr,
-                              (uint64_t)rot_index(member, j) * Lseg});
-        offsets.push_back(wins.back().w);
+        shard_of[nwin] = j;
+        wins[nwin++] = WinSpec{false, (uint64_t)rot_index(member, j) * Lseg};
     }
-    reft_plan *d = nullptr;
-    if ((rc = derived_plan(p, (1ull << 56) | ((uint64_t)k << 32) | member, offsets, Lseg, &d)))
+    const DerivedPlan *dp = nullptr;
+    if ((rc = derived_plan(p, (1ull << 56) | ((uint64_t)k << 32) | member, wins, nwin, Lseg, &dp)))
         return rc;
-    // (the end of the stream inside a window is a boundary too, because off[T] = L: the zero
-    // extension of the last segment starts on a piece boundary)
-    std::vector<const void *> rows((size_t)wins.size() * d->T);
-    for (size_t r = 0; r < wins.size(); ++r)
-        if ((rc = window_row(p, d, wins[r], rows.data() + r * d->T))) return rc;
-    return xor_rows(d, rows.data(), (uint32_t)wins.size(), nullptr, parity_dev, (hipStream_t)stream);
+    reft_plan *d = dp->plan;
+    const void **rows = d->row_buf.data();
+    for (uint32_t q = 0; q < nwin; ++q)
+        if ((rc = window_row(p, *dp, q, shard_span_ptrs + (size_t)shard_of[q] * p->T, nullptr,
+                             rows + (size_t)q * d->T)))
+            return rc;
+    return xor_rows(d, rows, nwin, nullptr, parity_dev, (hipStream_t)stream);
     REFT_GUARD_END("reft_parity_encode_rotated")
 }
 
@@ -1261,7 +1587,6 @@ extern "C" int reft_reconstruct_rotated(reft_plan *p, const void *const *shard_s
     if ((rc = check_span_ptrs(p, out_span_ptrs, 1, "reft_reconstruct_rotated(out)"))) return rc;
     const uint64_t Lseg = reft_segment_bytes(p, k);
     if (Lseg == 0) return REFT_OK;
-    if ((rc = ensure_zeros(p))) return rc;
     for (uint32_t r = 0; r + 1 < k; ++r) {
         const uint64_t o0 = (uint64_t)r * Lseg;
         if (o0 >= p->L) break;
@@ -1269,28 +1594,35 @@ extern "C" int reft_reconstruct_rotated(reft_plan *p, const void *const *shard_s
         const uint32_t i = r < lost ? r : r + 1;          // the member that protects segment r
         if (!parity_ptrs[i])
             return fail(REFT_EINVAL, "reft_reconstruct_rotated: parity unit of member %u is null", i);
-        std::vector<Window> wins;
-        std::vector<uint64_t> offsets;
-        wins.push_back(Window{nullptr, parity_ptrs[i], 0});
+        // windows: the parity unit, the other segments it covers, and last the destination (its
+        // own span boundaries must be piece boundaries too)
+        WinSpec wins[REFT_MAX_K + 1];
+        uint32_t shard_of[REFT_MAX_K + 1];
+        uint32_t nwin = 0;
+        shard_of[nwin] = 0;
+        wins[nwin++] = WinSpec{true, 0};
         for (uint32_t j = 0; j < k; ++j) {
             if (j == i || j == lost) continue;
-            wins.push_back(Window{shard_span_ptrs + (size_t)j * p->T, nullptr,
-                                  (uint64_t)rot_index(i, j) * Lseg});
-            offsets.push_back(wins.back().w);
+            shard_of[nwin] = j;
+            wins[nwin++] = WinSpec{false, (uint64_t)rot_index(i, j) * Lseg};
         }
-        offsets.push_back(o0);                            // the destination's own span boundaries
-        reft_plan *d = nullptr;
+        shard_of[nwin] = lost;
+        wins[nwin++] = WinSpec{false, o0};
+        const DerivedPlan *dp = nullptr;
         if ((rc = derived_plan(p, (2ull << 56) | ((uint64_t)k << 32) | ((uint64_t)lost << 16) | r,
-                               offsets, len, &d)))
+                               wins, nwin, len, &dp)))
             return rc;
-        std::vector<const void *> rows((size_t)wins.size() * d->T), dst(d->T);
-        for (size_t q = 0; q < wins.size(); ++q)
-            if ((rc = window_row(p, d, wins[q], rows.data() + q * d->T))) return rc;
-        const Window out_win{(const void *const *)out_span_ptrs, nullptr, o0};
-        if ((rc = window_row(p, d, out_win, dst.data()))) return rc;
-        if ((rc = xor_rows(d, rows.data(), (uint32_t)wins.size(), dst.data(), nullptr,
-                           (hipStream_t)stream)))
+        reft_plan *d = dp->plan;
+        const void **rows = d->row_buf.data();
+        if ((rc = window_row(p, *dp, 0, nullptr, parity_ptrs[i], rows))) return rc;
+        for (uint32_t q = 1; q + 1 < nwin; ++q)
+            if ((rc = window_row(p, *dp, q, shard_span_ptrs + (size_t)shard_of[q] * p->T, nullptr,
+                                 rows + (size_t)q * d->T)))
+                return rc;
+        const void **dst = rows + (size_t)(nwin - 1) * d->T;      // where xor_rows wants it anyway
+        if ((rc = window_row(p, *dp, nwin - 1, (const void *const *)out_span_ptrs, nullptr, dst)))
             return rc;
+        if ((rc = xor_rows(d, rows, nwin - 1, dst, nullptr, (hipStream_t)stream))) return rc;
     }
     return REFT_OK;
     REFT_GUARD_END("reft_reconstruct_rotated")
@@ -1336,24 +1668,12 @@ extern "C" int reft_reconstruct(const void *const *shards, uint32_t k, const voi
     uint32_t *ring = nullptr;
     int num_cus = 256;
     if (burst_ok) {
-        // counter blocks from a ring per device, allocated on first use and kept until the
-        // process ends
-        static std::mutex mu;
-        static std::map<int, std::pair<uint32_t *, int>> rings;   // device -> (ring, compute units)
-        int dev = 0;
-        HIPCHK(hipGetDevice(&dev));
-        std::lock_guard<std::mutex> lock(mu);
-        auto it = rings.find(dev);
-        if (it == rings.end()) {
-            uint32_t *r = nullptr;
-            hipDeviceProp_t prop;
-            HIPCHK(hipGetDeviceProperties(&prop, dev));
-            HIPCHK(hipMalloc((void **)&r, kCtrBlocks * kBurstCtrBytes));
-            it = rings.emplace(dev, std::make_pair(r, prop.multiProcessorCount > 0
-                                                          ? prop.multiProcessorCount : 256)).first;
-        }
-        ring = it->second.first;
-        num_cus = it->second.second;
+        // counter blocks from the ring in the library's static device memory (no allocation)
+        const DeviceStatics *ds = nullptr;
+        int rc = device_statics(&ds);
+        if (rc) return rc;
+        ring = ds->ctr;
+        num_cus = ds->num_cus;
     }
     static std::atomic<uint32_t> next_slot{0};
     uint32_t done = 0;
@@ -1365,7 +1685,7 @@ extern "C" int reft_reconstruct(const void *const *shards, uint32_t k, const voi
         if (burst_ok && (uint32_t)m >= g_burst_min_rows.load()) {
             // reads and writes separated in time; folding in place is safe: a stage of the
             // output is read and, a round later, written by the same workgroup only
-            bc = burst_cfg(ring, next_slot++, num_cus);
+            bc = burst_cfg(ring, next_slot++ % kCtrBlocks, num_cus);
             HIPCHK(launch_xor_contig_burst(b, m, (uint64_t)(uintptr_t)out_dev, L, cfg, bc, st));
         } else {
             HIPCHK(launch_xor_contig(b, m, (uint64_t)(uintptr_t)out_dev, L, tile_shift, cfg, st));
@@ -1392,7 +1712,7 @@ extern "C" int reft_reconstruct_spans(reft_plan *p, const void *const *shard_spa
     if ((rc = check_span_ptrs(p, out_span_ptrs, 1, "reft_reconstruct_spans(out)"))) return rc;
     // rows: the k-1 survivors, then the parity expressed as a span row
     const uint64_t T = p->T;
-    std::vector<const void *> rows((size_t)k * T);
+    const void **rows = p->row_buf.data();                     // (REFT_MAX_K + 1) * T entries
     uint32_t r = 0;
     for (uint32_t s = 0; s < k; ++s) {
         if (s == lost) continue;
@@ -1406,8 +1726,7 @@ extern "C" int reft_reconstruct_spans(reft_plan *p, const void *const *shard_spa
     for (uint64_t t = 0; t < T; ++t)
         rows[(size_t)r * T + t] = (const uint8_t *)parity_dev + p->off[t];
     ++r;                                                       // r == k source rows
-    return xor_rows(p, rows.data(), k, (const void *const *)out_span_ptrs, nullptr,
-                    (hipStream_t)stream);
+    return xor_rows(p, rows, k, (const void *const *)out_span_ptrs, nullptr, (hipStream_t)stream);
     REFT_GUARD_END("reft_reconstruct_spans")
 }
 
@@ -1442,15 +1761,15 @@ extern "C" int reft_restore(reft_plan *p, const void *host_src, uint64_t host_by
         cfg.max_wgs *= 2;          // reads across the link need about twice the waves of writes
         for (uint64_t b = 0; b < p->NB; ++b)
             HIPCHK(launch_scatter(pt, tab, hview, p->bstart[b], p->bstart[b + 1], cfg, us));
-        if ((rc = record(p->ring_ev[entry], us))) return rc;
+        if ((rc = release_ptrs(p, entry, us))) return rc;
         return record(p->rest_done, us);
     }
 
     int nslots = 1;
     if ((rc = staging_slots(p, staging, staging_bytes, "reft_restore", &nslots))) return rc;
-    std::vector<Run> runs;
-    std::vector<Dma> dmas;
-    classify_pieces(p, 0, p->NB, runs, dmas);
+    const PieceLists &pl = pieces_of(p, 0, p->NB);
+    const std::vector<Run> &runs = pl.runs;
+    const std::vector<Dma> &dmas = pl.dmas;
     const uint64_t stride = slot_stride(p);
     // The tensors are written on both streams.  The caller orders unpack_stream behind their last
     // use; copy_stream joins unpack_stream here so the same ordering covers its copies.
@@ -1498,7 +1817,7 @@ extern "C" int reft_restore(reft_plan *p, const void *host_src, uint64_t host_by
             }
             if ((rc = record(p->rest_free[g], us))) return rc;
         }
-        if ((rc = record(p->ring_ev[entry], us))) return rc;
+        if ((rc = release_ptrs(p, entry, us))) return rc;
     }
     // completion on unpack_stream: behind the scatter kernels and behind every direct copy
     if ((rc = record(p->rest_copied, cs))) return rc;

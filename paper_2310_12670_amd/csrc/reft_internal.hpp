@@ -36,6 +36,9 @@ struct BurstCfg {
     uint32_t nap;                  // pause between polls, in units of 1024 cycles
 };
 constexpr size_t kBurstCtrBytes = 9 * 64 * sizeof(uint32_t);
+// Words kBurstDiagWord .. +2 of a counter block (a cache line of their own, behind the polled
+// counter) receive the launch's diagnostics: writer-wave rounds that met, timed out, did not wait.
+constexpr uint32_t kBurstDiagWord = 8 * 64 + 32;
 
 // Sources passed by value for the contiguous XOR kernel.
 struct SrcBases {

@@ -474,6 +474,10 @@ __device__ __forceinline__ void burst_rounds(uint64_t nstages, uint32_t stage, u
     const uint32_t members = (G - g + 7) >> 3;         // workgroups that arrive on counter g
     const uint32_t ngroups = G < 8 ? G : 8;
     uint32_t skip = 0, backoff = 0;                    // writer wave: rounds left without waiting
+    // writer wave, lane 0: how its rounds went (met, timed out, not waited), kept in LDS behind
+    // the two images so that the bookkeeping costs the kernels no registers
+    REFT_LDS uint32_t *tally = (REFT_LDS uint32_t *)(lds + 2 * half);
+    if (threadIdx.x == kThreads) tally[0] = tally[1] = tally[2] = 0;
 
     for (uint64_t r = 0; r <= rounds; ++r) {
         if (!writer) {
@@ -482,6 +486,7 @@ __device__ __forceinline__ void burst_rounds(uint64_t nstages, uint32_t stage, u
         } else if (r > 0) {
             if (skip) {
                 --skip;
+                if (lane == 0) tally[2] += 1;
             } else if (max_polls) {
                 const uint32_t want = ngroups * (uint32_t)r;   // every group done with round r-1
                 for (uint32_t n = 0;;) {
@@ -490,11 +495,16 @@ __device__ __forceinline__ void burst_rounds(uint64_t nstages, uint32_t stage, u
                         v = __hip_atomic_load(ctr + 8 * kCtrStride, __ATOMIC_RELAXED,
                                               __HIP_MEMORY_SCOPE_AGENT);
                     v = __builtin_amdgcn_readfirstlane(v);
-                    if (v >= want) { backoff = 0; break; }
+                    if (v >= want) {
+                        backoff = 0;
+                        if (lane == 0) tally[0] += 1;
+                        break;
+                    }
                     if (++n >= max_polls) {
                         // a straggler: write without the others for 1, 2, 4, ... 64 rounds
                         backoff = backoff == 0 ? 1 : backoff < 64 ? backoff * 2 : 64;
                         skip = backoff;
+                        if (lane == 0) tally[1] += 1;
                         break;
                     }
                     for (uint32_t z = 0; z < nap; ++z) __builtin_amdgcn_s_sleep(16);
@@ -511,6 +521,14 @@ __device__ __forceinline__ void burst_rounds(uint64_t nstages, uint32_t stage, u
                 __hip_atomic_fetch_add(ctr + 8 * kCtrStride, 1u, __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
         }
+    }
+    // diagnostics (three adds per workgroup and launch): rounds in which the writer wave saw the
+    // meeting complete, ran out of polls, or did not wait at all
+    if (writer && lane == 0 && max_polls) {
+        uint32_t *diag = ctr + kBurstDiagWord;
+        __hip_atomic_fetch_add(diag + 0, tally[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(diag + 1, tally[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(diag + 2, tally[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -726,7 +744,7 @@ static bool burst_cfg_ok(const BurstCfg &bc)
 static hipError_t burst_grid(const void *fn, uint64_t nstages, const LaunchCfg &cfg,
                              const BurstCfg &bc, size_t *lds, uint32_t *grid)
 {
-    *lds = 2 * ((size_t)bc.stage_bytes + 16);
+    *lds = 2 * ((size_t)bc.stage_bytes + 16) + 16;      // two images and the writer's tally
     int per_cu = 0;
     hipError_t e = burst_occupancy(fn, *lds, &per_cu);
     if (e != hipSuccess) return e;

@@ -43,6 +43,7 @@ def test_every_member_is_restored_from_its_duplicate(staged):
         for lost in range(k):
             holder = (lost - 1) % k
             fresh = [torch.zeros_like(t) for t in shards[lost]]
+            torch.cuda.synchronize()         # the zero fill runs on another stream than the restore
             reft.reft_restore(plan, dup[holder], staging, fresh, s_b, s_a)
             reft.reft_restore_wait(plan)
             want = oracle.unpack(streams[lost], sizes)

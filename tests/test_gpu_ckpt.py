@@ -154,6 +154,69 @@ def test_completed_and_ongoing_snapshots(dev):
         reft.reft_plan_destroy(plan)
 
 
+def test_begin_is_refused_while_a_commit_is_in_flight(dev):
+    """A second snapshot may not begin before the first one's COMPLETED mark has landed: until then
+    neither buffer may be overwritten.  The commit is held back from the host by a long sleep kernel
+    queued in front of it; every kernel ends normally."""
+    wl, sizes, plan, staging = setup(dev)
+    try:
+        L = wl.L
+        shard = fill_shard(wl, 0, dev)
+        want = oracle.pack([oracle.as_bytes(t.cpu()) for t in shard])
+        bufs = [torch.full((L,), CANARY, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        ck = reft.reft_ckpt_create(plan, bufs[0], bufs[1])
+        try:
+            dst, gen = reft.reft_ckpt_begin(ck)
+            reft.reft_snapshot_pack(plan, shard, staging, dst, s1, s2, host_cap=L)
+            with torch.cuda.stream(s2):
+                torch.cuda._sleep(100_000_000)           # tens of milliseconds in front of the commit
+            reft.reft_ckpt_commit(ck, s2)
+            with pytest.raises(reft.ReftError) as e:
+                reft.reft_ckpt_begin(ck)
+            assert e.value.code == reft.REFT_EBUSY
+            assert reft.reft_ckpt_latest(ck) == (None, 0)
+            reft.reft_ckpt_wait(ck)
+            assert reft.reft_ckpt_latest(ck) == (dst, gen)
+            assert np.array_equal(host_view(dst, L), want)
+            dst2, gen2 = reft.reft_ckpt_begin(ck)        # accepted now, into the other buffer
+            assert gen2 == gen + 1 and dst2 != dst
+            # destroying with a commit still queued waits for it instead of freeing its flag
+            reft.reft_snapshot_pack(plan, shard, staging, dst2, s1, s2, host_cap=L)
+            with torch.cuda.stream(s2):
+                torch.cuda._sleep(50_000_000)
+            reft.reft_ckpt_commit(ck, s2)
+        finally:
+            reft.reft_ckpt_destroy(ck)
+        torch.cuda.synchronize()
+        assert np.array_equal(bufs[0].numpy() if dst2 == bufs[0].data_ptr() else bufs[1].numpy(), want)
+    finally:
+        reft.reft_plan_destroy(plan)
+
+
+def test_snapshot_wait_covers_calls_on_different_streams(dev):
+    """Two range calls of one snapshot that end on different streams: reft_snapshot_wait returns
+    only when both have landed."""
+    wl, sizes, plan, staging = setup(dev)
+    try:
+        L, nb = wl.L, reft.reft_plan_num_buckets(plan)
+        shard = fill_shard(wl, 2, dev)
+        want = oracle.pack([oracle.as_bytes(t.cpu()) for t in shard])
+        host = torch.full((L,), CANARY, dtype=torch.uint8, pin_memory=True)
+        s1, s2, s3 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s2):
+            torch.cuda._sleep(100_000_000)               # the first call's copies start late
+        reft.reft_snapshot_pack_range(plan, shard, staging, host, 0, nb // 2, s1, s2, host_cap=L)
+        reft.reft_snapshot_pack_range(plan, shard, None, host, nb // 2, nb, s3, None, host_cap=L)
+        reft.reft_snapshot_wait(plan)
+        assert np.array_equal(host.numpy(), want)
+        torch.cuda.synchronize()
+    finally:
+        reft.reft_plan_destroy(plan)
+
+
 @pytest.mark.parametrize("mode", [1, 2, 0])
 def test_replayed_copy_graphs_follow_the_data(dev, mode):
     """The staged transport replays its piece copies as a cached hipGraph when a call repeats the

@@ -1,4 +1,5 @@
-"""GPU parity at the full sizes of configurations 1-4, in the launch configuration bench.py times.
+"""GPU parity at the full sizes of configurations 1-4, in the launch configuration bench.py times
+(staged snapshot, staged restore, write-burst XOR kernels), plus the direct restore.
 
 At 11-15 GB per shard the oracle cannot recompute everything in seconds, so each case checks
   * sampled windows of every output against the oracle, byte for byte: random windows, windows
@@ -165,15 +166,29 @@ def run_full(dev, cfg, do_reconstruct, with_gemm=False):
         assert torch.equal(host_par.to(dev), parity)
         say("full-size properties ok (host == tensors, zero-sum, parity snapshot)")
 
-        # -- load phase: direct restore of the own shard and the parity, fused decode of the lost one
-        fresh = [torch.empty_like(t) for t in shards[own]]
-        parity2 = torch.empty_like(parity)
-        reft.reft_restore(plan, host, None, fresh, None, s_load)
-        reft.reft_restore(pplan, host_par, None, [parity2], None, s_load)
-        reft.reft_restore_wait(pplan)
-        torch.cuda.synchronize()
-        assert all(torch.equal(a, b) for a, b in zip(fresh, shards[own])), "restore"
-        assert torch.equal(parity2, parity)
+        # -- load phase, once with each transport (bench.py times the staged one): restore of the
+        #    own shard and of the parity, oracle windows on the restored tensors, every byte with torch
+        lstaging = torch.empty(nslots * slot, dtype=torch.uint8, device=dev)
+        for mode, stg, pstg, s_cp in (("staged", lstaging, pstaging, s_copy), ("direct", None, None, None)):
+            fresh = [torch.empty_like(t) for t in shards[own]]
+            parity2 = torch.empty_like(parity)
+            for t in fresh:
+                t.view(torch.uint8).fill_(0xA5)
+            parity2.fill_(0xA5)
+            torch.cuda.synchronize()
+            reft.reft_restore(plan, host, stg, fresh, s_cp, s_load)
+            reft.reft_restore(pplan, host_par, pstg, [parity2], s_cp, s_load)
+            reft.reft_restore_wait(plan)
+            reft.reft_restore_wait(pplan)
+            torch.cuda.synchronize()
+            for (a, b), (p, win) in par_ref.items():
+                got = oracle.pack(stream_window(fresh, offs, a, b))
+                assert np.array_equal(got, win[own]), f"{mode} restore window [{a},{b})"
+                assert np.array_equal(parity2[a:b].cpu().numpy(), p), f"{mode} parity restore window [{a},{b})"
+            assert all(torch.equal(a, b) for a, b in zip(fresh, shards[own])), f"{mode} restore"
+            assert torch.equal(parity2, parity), f"{mode} restore of the parity"
+            say(f"{mode} restore ok ({len(par_ref)} oracle windows, every byte with torch)")
+        del lstaging
         del fresh
         if do_reconstruct:
             out = [torch.empty_like(t) for t in shards[lost]]
@@ -282,11 +297,22 @@ def test_config4_recovery_from_host(dev):
             for (a, b), win in ref_win.items():
                 assert np.array_equal(hnp[a:b], win[s]), f"snapshot {s} window [{a},{b})"
 
+        residency = "all survivors host-resident" if all_resident else \
+            f"fallback, {len(hosts)} of {k} shards host-resident at a time"
+
         def restore(s, hbuf):
+            # survivors alternate between the two transports
+            staged = s % 2 == 0
+            mode = f"{'staged' if staged else 'direct'} restore of shard {s} ({residency})"
             fresh = [torch.empty_like(t) for t in shards[s]]
-            reft.reft_restore(plan, hbuf, None, fresh, None, s_load)
-            s_load.synchronize()
-            assert all(torch.equal(a, b) for a, b in zip(fresh, shards[s])), f"restore shard {s}"
+            reft.reft_restore(plan, hbuf, staging if staged else None, fresh,
+                              s_copy if staged else None, s_load)
+            reft.reft_restore_wait(plan)
+            torch.cuda.synchronize()
+            for (a, b), win in ref_win.items():
+                assert np.array_equal(oracle.pack(stream_window(fresh, offs, a, b)), win[s]), \
+                    f"{mode}: window [{a},{b})"
+            assert all(torch.equal(a, b) for a, b in zip(fresh, shards[s])), mode
             shards[s] = fresh                       # the restored copy is the shard from here on
             gc.collect()
             torch.cuda.empty_cache()
@@ -318,11 +344,12 @@ def test_config4_recovery_from_host(dev):
         rows = [t for s in range(k) for t in (shards[s] if s != lost else [None] * len(sizes))]
         reft.reft_reconstruct_spans(plan, rows, k, lost, parity2, out, s_xor)
         s_xor.synchronize()
-        assert all(torch.equal(a, b) for a, b in zip(out, originals_lost)), "reconstructed shard"
+        assert all(torch.equal(a, b) for a, b in zip(out, originals_lost)), \
+            f"reconstructed shard ({residency})"
         for (a, b), want in ref_lost.items():
             assert np.array_equal(oracle.pack(stream_window(out, offs, a, b)), want), \
-                f"reconstruct window [{a},{b})"
-        say("recovery ok: k-1 shards restored from host, lost shard decoded")
+                f"reconstruct window [{a},{b}) ({residency})"
+        say(f"recovery ok ({residency}): k-1 shards restored from host, lost shard decoded")
     finally:
         reft.reft_plan_destroy(plan)
         reft.reft_plan_destroy(pplan)

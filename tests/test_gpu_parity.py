@@ -30,13 +30,16 @@ def dev():
 
 
 @pytest.fixture(autouse=True, params=["direct", "staged", "staged-gather", "direct-lds",
-                                      "staged-gather-lds", "staged-tiny-dma"])
+                                      "staged-gather-lds", "staged-tiny-dma", "staged-2streams",
+                                      "staged-tiny-dma-2streams"])
 def default_tunables(request):
     """Every case runs with each host transport: direct (kernels touch pinned host memory),
     staged (large pieces by DMA from the tensors, runs of small pieces through gather kernel and
     staging ring), staged-gather (every byte through the gather kernel and the ring) and
-    staged-tiny-dma (every piece, however small, its own DMA copy); "-lds" forces the kernels'
-    LDS-staged small-piece path on for every tile.  Launch parameters are restored afterwards."""
+    staged-tiny-dma (every piece, however small, its own DMA copy); "-2streams" alternates the piece
+    copies between copy_stream and the plan's helper stream (dma_streams = 2); "-lds" forces the
+    kernels' LDS-staged small-piece path on for every tile.  Launch parameters are restored
+    afterwards."""
     global DIRECT
     names = ("max_wgs", "nontemporal", "unroll", "tile_shift", "link_wgs", "small_pieces",
              "dma_min_bytes", "gather_min_pieces", "dma_streams")
@@ -47,7 +50,7 @@ def default_tunables(request):
         reft.reft_set_tunable("gather_min_pieces", 1)
     if "-tiny-dma" in request.param:
         reft.reft_set_tunable("dma_min_bytes", 0)
-        reft.reft_set_tunable("dma_streams", 1)
+    reft.reft_set_tunable("dma_streams", 2 if request.param.endswith("-2streams") else 1)
     if request.param.endswith("-lds"):
         reft.reft_set_tunable("small_pieces", 0)
     yield

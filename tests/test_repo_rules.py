@@ -56,3 +56,25 @@ def test_bench_refuses_more_than_one_gpu():
                          capture_output=True, text=True, timeout=120)
     assert res.returncode != 0
     assert "ONE GPU" in res.stderr
+
+
+def test_only_the_diagnostic_call_waits_for_the_whole_device():
+    """Data-moving entry points neither wait for the whole device nor allocate device or pinned
+    memory: hipDeviceSynchronize appears in reft_plan_burst_stats only, and the allocating calls
+    are confined to plan / checkpoint creation and the set-up of derived tables."""
+    text = open(os.path.join(ROOT, "paper_2310_12670_amd", "csrc", "reft_api.hip")).read()
+    # function bodies by name: text between one top-level definition and the next
+    starts = [(m.start(), m.group(1)) for m in re.finditer(
+        r"^(?:extern \"C\" |static |template <[^>]*>\nstatic )[^\n;{]*?\b(\w+)\([^;{]*\)\n\{", text, re.M)]
+    bodies = {}
+    for (a, name), (b, _) in zip(starts, starts[1:] + [(len(text), "")]):
+        bodies.setdefault(name, "")
+        bodies[name] += text[a:b]
+    assert "reft_snapshot_pack_range" in bodies and "upload_ptrs" in bodies and "xor_rows" in bodies
+    sync_in = sorted(n for n, b in bodies.items() if "hipDeviceSynchronize" in b)
+    assert sync_in == ["reft_plan_burst_stats"], sync_in
+    alloc_in = sorted(n for n, b in bodies.items()
+                      if re.search(r"\bhip(Malloc|HostMalloc|ExtMallocWithFlags|MallocAsync)\(", b))
+    assert alloc_in == ["ensure_zeros", "reft_ckpt_create", "reft_plan_create"], alloc_in
+    assert "hipMalloc" not in open(os.path.join(ROOT, "paper_2310_12670_amd", "csrc",
+                                                "reft_kernels.hip")).read()
