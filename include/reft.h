@@ -222,6 +222,26 @@ int reft_unpack_device(reft_plan *plan, const void *src_dev, uint64_t src_bytes,
 int reft_parity_encode(reft_plan *plan, const void *const *shard_span_ptrs, uint32_t k,
                        void *parity_dev, reft_stream stream);
 
+/* ---- reft_parity_encode for callers that cannot allocate ------------------------------------------
+ * For code that may not call hipMalloc while it runs: work under HIP graph capture, tight serving
+ * loops, harnesses that forbid allocation.  Same arguments, same result as reft_parity_encode; the
+ * call itself allocates no device or pinned memory, frees none, uses none of the plan's caches
+ * and records no event.  What reft_parity_encode keeps in buffers the plan allocated - the device
+ * copy of the span pointers and the write-burst kernels' counters - lives here in a static device
+ * array of the library, 258.5 KiB (256 KiB of pointers, then one counter block), which every GPU
+ * the library runs on holds until the process ends.  The pointers reach it as arguments of
+ * small kernels (256 per launch) on `stream`; the counters are cleared by a kernel before each
+ * XOR launch.
+ * Limit: k * T <= 32768 span pointers, else REFT_ESIZE.
+ * All calls on one GPU share the array: a call must not overlap, on another stream or from
+ * another thread, with another call of this function on the same GPU (the later one would
+ * overwrite the pointer table the earlier one still reads).  Calls on one stream are ordered.
+ * The plan must have been created on the current GPU (that is when the array's device address
+ * is looked up).  Other errors as reft_parity_encode.
+ */
+int reft_parity_encode_noalloc(reft_plan *plan, const void *const *shard_span_ptrs, uint32_t k,
+                               void *parity_dev, reft_stream stream);
+
 /* ---- S6: decode the single lost shard (section 4.2, Eq. 2) ---------------------------------------
  * out_dev[i] = parity[i] ^ (XOR over the surviving shards s of shards[s][i]), i in [0, L).
  *

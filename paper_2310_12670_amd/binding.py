@@ -23,7 +23,8 @@ __all__ = [
     "reft_snapshot_query", "reft_ckpt_create", "reft_ckpt_destroy", "reft_ckpt_begin",
     "reft_ckpt_commit", "reft_ckpt_latest", "reft_ckpt_wait", "REFT_EBUSY",
     "reft_plan_staged_work", "reft_plan_burst_stats",
-    "reft_pack_device", "reft_unpack_device", "reft_parity_encode", "reft_reconstruct",
+    "reft_pack_device", "reft_unpack_device", "reft_parity_encode", "reft_parity_encode_noalloc",
+    "reft_reconstruct",
     "reft_reconstruct_spans", "reft_segment_bytes", "reft_parity_encode_rotated",
     "reft_reconstruct_rotated", "reft_restore", "reft_restore_wait",
     "reft_set_tunable", "reft_get_tunable", "reft_last_error", "reft_version",
@@ -85,6 +86,7 @@ def _load():
         "reft_pack_device": (i, [vp, vp, vp, u64, vp]),
         "reft_unpack_device": (i, [vp, vp, u64, vp, vp]),
         "reft_parity_encode": (i, [vp, vp, u32, vp, vp]),
+        "reft_parity_encode_noalloc": (i, [vp, vp, u32, vp, vp]),
         "reft_plan_staged_work": (i, [vp, pu64, pu64]),
         "reft_plan_burst_stats": (i, [vp, pu64]),
         "reft_ckpt_wait": (i, [vp]),
@@ -324,6 +326,11 @@ def reft_parity_encode(plan, shard_span_ptrs, k: int, parity_dev, stream=None) -
     """``shard_span_ptrs``: k*T entries, row-major (entry s*T + t = span t of shard s)."""
     _check(_load().reft_parity_encode(plan, ptr_array(shard_span_ptrs), int(k), _addr(parity_dev),
                                       _stream(stream)))
+
+
+def reft_parity_encode_noalloc(plan, shard_span_ptrs, k: int, parity_dev, stream=None) -> None:
+    _check(_load().reft_parity_encode_noalloc(plan, ptr_array(shard_span_ptrs), int(k),
+                                              _addr(parity_dev), _stream(stream)))
 
 
 def reft_reconstruct(shards, parity, L: int, out_dev, stream=None) -> int:

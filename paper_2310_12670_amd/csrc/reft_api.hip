@@ -242,6 +242,8 @@ struct reft_plan {
     uint64_t pieces_tick = 0;
     // stream on which the most recent snapshot's completion event was recorded
     hipStream_t last_pack_stream = nullptr;
+    // device address of the library's static scratch on this plan's GPU (see reft_parity_encode_noalloc)
+    unsigned char *scratch = nullptr;
     // ring of burst counter blocks in static device memory, shared by all plans of the GPU
     uint32_t *static_ctr = nullptr;
     // bucket pipelines
@@ -326,15 +328,23 @@ static int wait_on(hipStream_t s, const Event &e)
 // ------------------------------------------------------------------------------------------------
 // static device memory of the library
 // ------------------------------------------------------------------------------------------------
-// `static_ctr` is the ring of burst counter blocks of reft_reconstruct, which has no plan to keep
-// them in.  In host code the name is a stand-in, not a device address: the address comes from
-// hipGetSymbolAddress, once per device.
+// `scratch` serves reft_parity_encode_noalloc, the entry point for callers that cannot allocate:
+// a table of up to kScratchPtrs span pointers, then one block of burst counters.  Every GPU the
+// library runs on holds its own copy until the process ends.  `static_ctr` is the ring of counter
+// blocks of reft_reconstruct, which has no plan to keep them in.  In host code these names are
+// stand-ins, not device addresses: the addresses come from hipGetSymbolAddress, once per device.
+constexpr uint32_t kScratchPtrs = 32768;
+constexpr size_t kScratchPtrBytes = (size_t)kScratchPtrs * sizeof(uint64_t);
+constexpr size_t kScratchBytes = kScratchPtrBytes + 2560;            // 256 KiB + counters
+static_assert(kBurstCtrBytes <= 2560, "the counter block must fit behind the pointer table");
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 static __device__ __align__(256) uint32_t static_ctr[kCtrBlocks * (kBurstCtrBytes / sizeof(uint32_t))];
 
 namespace {
 constexpr int kMaxDevices = 64;
 struct DeviceStatics {
     bool known = false;
+    unsigned char *scratch = nullptr;
     uint32_t *ctr = nullptr;
     int num_cus = 256;
 };
@@ -351,11 +361,13 @@ static int device_statics(const DeviceStatics **out)
     std::lock_guard<std::mutex> lock(g_statics_mu);
     DeviceStatics &d = g_statics[dev];
     if (!d.known) {
-        void *b = nullptr;
+        void *a = nullptr, *b = nullptr;
+        HIPCHK(hipGetSymbolAddress(&a, HIP_SYMBOL(scratch)));
         HIPCHK(hipGetSymbolAddress(&b, HIP_SYMBOL(static_ctr)));
-        if (!b) return fail(REFT_EHIP, "hipGetSymbolAddress returned a null address");
+        if (!a || !b) return fail(REFT_EHIP, "hipGetSymbolAddress returned a null address");
         hipDeviceProp_t prop;
         HIPCHK(hipGetDeviceProperties(&prop, dev));
+        d.scratch = (unsigned char *)a;
         d.ctr = (uint32_t *)b;
         d.num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
         d.known = true;
@@ -603,6 +615,7 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
     int rc;
     const DeviceStatics *ds = nullptr;
     if ((rc = device_statics(&ds))) return rc;
+    p->scratch = ds->scratch;
     p->static_ctr = ds->ctr;
     for (int i = 0; i < kRing; ++i) {
         if ((rc = make_event(p->ring[i].uploaded))) return rc;
@@ -1428,6 +1441,57 @@ extern "C" int reft_parity_encode(reft_plan *p, const void *const *shard_span_pt
     if (!parity_dev) return fail(REFT_EINVAL, "reft_parity_encode: null parity buffer");
     return xor_rows(p, shard_span_ptrs, k, nullptr, parity_dev, (hipStream_t)stream);
     REFT_GUARD_END("reft_parity_encode")
+}
+
+// ------------------------------------------------------------------------------------------------
+// S4 for callers that cannot allocate
+// ------------------------------------------------------------------------------------------------
+namespace {
+constexpr uint32_t kPtrChunk = 256;
+struct PtrChunk {
+    uint64_t p[kPtrChunk];
+};
+}  // namespace
+
+// Pointers travel to the device as kernel arguments, 256 at a time: no pinned staging, nothing the
+// call would have to keep alive, and the launch is an ordinary kernel node for a capturing caller.
+__global__ void k_store_ptrs(uint64_t *dst, PtrChunk c, uint32_t n)
+{
+    if (threadIdx.x < n) dst[threadIdx.x] = c.p[threadIdx.x];
+}
+
+extern "C" int reft_parity_encode_noalloc(reft_plan *p, const void *const *shard_span_ptrs,
+                                          uint32_t k, void *parity_dev, reft_stream stream)
+{
+    int rc = check_plan(p, "reft_parity_encode_noalloc");
+    if (rc) return rc;
+    if (k < 1 || k > REFT_MAX_K)
+        return fail(REFT_EINVAL, "reft_parity_encode_noalloc: k = %u outside [1, %d]", k, REFT_MAX_K);
+    const uint64_t n = (uint64_t)k * p->T;
+    if (n > kScratchPtrs)
+        return fail(REFT_ESIZE, "reft_parity_encode_noalloc: k * T = %llu span pointers, the static "
+                                "scratch holds %u", (unsigned long long)n, kScratchPtrs);
+    if ((rc = check_span_ptrs(p, shard_span_ptrs, k, "reft_parity_encode_noalloc"))) return rc;
+    if (p->L == 0) return REFT_OK;
+    if (!parity_dev) return fail(REFT_EINVAL, "reft_parity_encode_noalloc: null parity buffer");
+    if (!p->scratch) return fail(REFT_EINVAL, "reft_parity_encode_noalloc: no static scratch on this GPU");
+    hipStream_t s = (hipStream_t)stream;
+    // p->scratch is the device address of `scratch` on the plan's GPU (hipGetSymbolAddress at plan
+    // creation): the pointer table first, one block of burst counters behind it.  The table is
+    // overwritten here and the counters are cleared by a kernel before each burst launch, so
+    // nothing of an earlier call survives into this one.
+    uint64_t *tab = (uint64_t *)p->scratch;
+    uint32_t *ctr = (uint32_t *)(p->scratch + kScratchPtrBytes);
+    for (uint64_t i = 0; i < n; i += kPtrChunk) {
+        PtrChunk c;
+        const uint32_t m = (uint32_t)(n - i < kPtrChunk ? n - i : kPtrChunk);
+        for (uint32_t j = 0; j < m; ++j) c.p[j] = (uint64_t)(uintptr_t)shard_span_ptrs[i + j];
+        for (uint32_t j = m; j < kPtrChunk; ++j) c.p[j] = 0;
+        hipLaunchKernelGGL(k_store_ptrs, dim3(1), dim3(kPtrChunk), 0, s, tab + i, c, m);
+        HIPCHK(hipGetLastError());
+    }
+    uint32_t next = 0;
+    return xor_passes(p, tab, k, nullptr, nullptr, parity_dev, ctr, 1, &next, s);
 }
 
 // ------------------------------------------------------------------------------------------------
