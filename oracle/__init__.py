@@ -52,6 +52,7 @@ class Oracle:
         lib.oracle_segment_bytes.restype = u64
         lib.oracle_encode_rotated.argtypes = [p, u32, u64, u32, p]
         lib.oracle_reconstruct_rotated.argtypes = [p, p, u32, u64, u32, p]
+        lib.oracle_collab_recover.argtypes = [p, p, p, u32, p, u32, u64, p, p, p]
         self.lib = lib
 
     # -- threads for the optional outer-range split ------------------------------------------
@@ -144,6 +145,31 @@ class Oracle:
         return out
 
 
+    # -- collaborative protection (section 4.2, last paragraph) ------------------------------------
+    def collab_recover(self, shards: Sequence[Optional[np.ndarray]],
+                       dups: Sequence[Sequence[Optional[np.ndarray]]], arc_offsets: Sequence[int],
+                       units: Optional[Sequence[Optional[np.ndarray]]], lost: Sequence[int], L: int):
+        """``shards[i]`` / ``dups[a][i]`` / ``units[i]`` of lost members may be None (never read).
+        Returns (recovered, unknown, seg_known): the recovered shards by lost member, the number
+        of segments that stay unknown, and the k x (k-1) table of known segments."""
+        k = len(shards)
+        lost_flags = np.zeros(k, dtype=np.uint8)
+        lost_flags[list(lost)] = 1
+        dummy = np.zeros(1, dtype=np.uint8)
+        sh = [dummy if a is None else a for a in shards]
+        du = [dummy if a is None else a for row in dups for a in row]
+        un = None if units is None else [dummy if a is None else a for a in units]
+        out = [np.full(int(L), 0xEE, dtype=np.uint8) if lost_flags[i] else dummy for i in range(k)]
+        seg = np.zeros(k * (k - 1), dtype=np.uint8)
+        rc = self.lib.oracle_collab_recover(
+            _ptr_array(sh), _ptr_array(du), _u32_array(arc_offsets), len(arc_offsets),
+            None if un is None else _ptr_array(un), k, int(L), lost_flags.ctypes.data,
+            _ptr_array(out), seg.ctypes.data)
+        if rc < 0:
+            raise ValueError("oracle: collab_recover rejected its arguments")
+        return {i: out[i] for i in range(k) if lost_flags[i]}, int(rc), seg.reshape(k, k - 1)
+
+
 # ------------------------------------------------------------------------------------------------
 # marshalling helpers (no arithmetic)
 # ------------------------------------------------------------------------------------------------
@@ -160,6 +186,10 @@ def _ptr_array(arrays: Sequence[np.ndarray]):
     for a in arrays:
         assert a.dtype == np.uint8 and a.flags["C_CONTIGUOUS"]
     return (ctypes.c_void_p * max(1, len(arrays)))(*[a.ctypes.data for a in arrays])
+
+
+def _u32_array(vals: Sequence[int]):
+    return (ctypes.c_uint32 * max(1, len(vals)))(*[int(v) for v in vals])
 
 
 def _u64_array(vals: Sequence[int]):
@@ -196,3 +226,5 @@ def encode_rotated(shards, member):
     return default().encode_rotated(shards, member)
 def reconstruct_rotated(shards, parities, lost, L):
     return default().reconstruct_rotated(shards, parities, lost, L)
+def collab_recover(shards, dups, arc_offsets, units, lost, L):
+    return default().collab_recover(shards, dups, arc_offsets, units, lost, L)

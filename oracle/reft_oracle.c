@@ -231,3 +231,99 @@ int oracle_reconstruct_rotated(const uint8_t *const *shards, const uint8_t *cons
     return 0;
 }
 
+
+/*
+ * Collaborative redundant protection (section 4.2, last paragraph): several redundancy
+ * strategies enabled at once, or one strategy several times with different parameters, so that
+ * several members of a sharding group may fail.  What member i of a group of k keeps in its host
+ * memory, and loses with it:
+ *   - its own shard S_i;
+ *   - per enabled redundant copy (ARC) with offset d, 1 <= d < k: a duplicate of the shard of
+ *     member (i + d) mod k ("saves shards from peer members");
+ *   - if erasure coding (AEC) is enabled: its rotated parity unit U_i (oracle_encode_rotated).
+ * Recovery of the lost members' shards, in the order of the loading procedure (section 4.3: take
+ * what exists as a copy, decode the rest):
+ *   1. a lost shard S_x whose duplicate survives - on member (x - d) mod k for some enabled
+ *      offset d - is that duplicate;
+ *   2. what is still missing is decoded segment by segment with the subtraction decoder (Eq. 2):
+ *      segment r of S_x is covered by the unit of member i with r(i, x) = r; it can be decoded if
+ *      member i survives and every other segment that unit covers is known (its shard survived,
+ *      was copied in step 1, or the segment was decoded before); repeated until nothing changes.
+ * The paper states the tolerance ("N or fewer failures") without a procedure; which pairs of
+ * losses a given combination really survives is exactly what this function computes.
+ *
+ * shards[k]        surviving members' shards (entries of lost members are not read)
+ * dups[n_arc * k]  dups[a * k + i] = member i's duplicate under offset arc_offsets[a] (entries of
+ *                  lost members are not read)
+ * units[k]         the rotated parity units, or NULL if erasure coding is not enabled (entries
+ *                  of lost members are not read)
+ * lost[k]          1 = member lost
+ * out[k]           out[x] (L bytes) receives the recovered shard of lost member x; bytes of
+ *                  segments that cannot be recovered are left untouched
+ * seg_known[k * (k-1)]  receives 1 for every segment of every member's shard that is known at
+ *                  the end (all 1 for survivors)
+ * Returns the number of segments with stream bytes that stay unknown (0 = everything recovered),
+ * or -1 on an invalid argument.  k >= 2.
+ */
+int oracle_collab_recover(const uint8_t *const *shards, const uint8_t *const *dups,
+                          const uint32_t *arc_offsets, uint32_t n_arc,
+                          const uint8_t *const *units, uint32_t k, uint64_t L,
+                          const uint8_t *lost, uint8_t *const *out, uint8_t *seg_known)
+{
+    if (k < 2) return -1;
+    for (uint32_t a = 0; a < n_arc; ++a)
+        if (arc_offsets[a] < 1 || arc_offsets[a] >= k) return -1;
+    const uint32_t nseg = k - 1;
+    const uint64_t Lseg = oracle_segment_bytes(L, k);
+    for (uint32_t x = 0; x < k; ++x)
+        for (uint32_t r = 0; r < nseg; ++r) seg_known[x * nseg + r] = lost[x] ? 0 : 1;
+
+    /* step 1: redundant copies */
+    for (uint32_t x = 0; x < k; ++x) {
+        if (!lost[x] || seg_known[x * nseg]) continue;
+        for (uint32_t a = 0; a < n_arc; ++a) {
+            const uint32_t holder = (x + k - arc_offsets[a]) % k;   /* (holder + d) mod k == x */
+            if (lost[holder]) continue;
+            for (uint64_t o = 0; o < L; ++o) out[x][o] = dups[a * k + holder][o];
+            for (uint32_t r = 0; r < nseg; ++r) seg_known[x * nseg + r] = 1;
+            break;
+        }
+    }
+
+    /* step 2: erasure decoding, segment by segment, until nothing changes */
+    int progress = units != 0;
+    while (progress) {
+        progress = 0;
+        for (uint32_t x = 0; x < k; ++x) {
+            if (!lost[x]) continue;
+            for (uint32_t r = 0; r < nseg; ++r) {
+                if (seg_known[x * nseg + r]) continue;
+                const uint32_t i = r < x ? r : r + 1;               /* r(i, x) == r */
+                if (lost[i]) continue;
+                int ready = 1;
+                for (uint32_t j = 0; j < k; ++j)
+                    if (j != i && j != x && !seg_known[j * nseg + oracle_rot_index(i, j)]) ready = 0;
+                if (!ready) continue;
+                for (uint64_t t = 0; t < Lseg; ++t) {
+                    const uint64_t o = (uint64_t)r * Lseg + t;
+                    if (o >= L) break;
+                    uint8_t v = units[i][t];
+                    for (uint32_t j = 0; j < k; ++j) {
+                        if (j == i || j == x) continue;
+                        const uint64_t y = (uint64_t)oracle_rot_index(i, j) * Lseg + t;
+                        if (y < L) v ^= lost[j] ? out[j][y] : shards[j][y];
+                    }
+                    out[x][o] = v;
+                }
+                seg_known[x * nseg + r] = 1;
+                progress = 1;
+            }
+        }
+    }
+
+    int unknown = 0;
+    for (uint32_t x = 0; x < k; ++x)
+        for (uint32_t r = 0; r < nseg; ++r)
+            if (!seg_known[x * nseg + r] && (uint64_t)r * Lseg < L) ++unknown;
+    return unknown;
+}

@@ -354,7 +354,142 @@ def pin_rotated_bruteforce(orc):
                 assert got.tolist() == unit, (k, L, i)
 
 
+# ------------------------------------------------------------------------------------------------
+# collaborative protection (section 4.2, last paragraph)
+# ------------------------------------------------------------------------------------------------
+def _holdings(orc, shards, arc_offsets, aec):
+    k = len(shards)
+    dups = [[shards[(i + d) % k] for i in range(k)] for d in arc_offsets]
+    units = [orc.encode_rotated(shards, i) for i in range(k)] if aec else None
+    return dups, units
+
+
+def _survivors_only(rows, lost):
+    return [None if i in lost else a for i, a in enumerate(rows)]
+
+
+def pin_golden_collab(orc):
+    """The hand-worked cases: which segments come back, and their bytes."""
+    shards = [_hex(t) for k, t in _read_golden("rotated_parity_worked.txt") if k == "shard"]
+    k, L = len(shards), shards[0].size
+    rows = _read_golden("collab_recovery_worked.txt")
+    cases = []
+    for key, t in rows:
+        if key == "case":
+            offs = [] if t[0] == "-" else [int(x) for x in t[0].split(",")]
+            cases.append({"offs": offs, "aec": t[1] == "1", "lost": [int(x) for x in t[2].split(",")],
+                          "unknown": int(t[3]), "rec": {}})
+        else:
+            cases[-1]["rec"][int(t[0])] = t[1:]
+    assert len(cases) == 7
+    for c in cases:
+        dups, units = _holdings(orc, shards, c["offs"], c["aec"])
+        rec, unknown, seg = orc.collab_recover(
+            _survivors_only(shards, c["lost"]), [_survivors_only(d, c["lost"]) for d in dups],
+            c["offs"], None if units is None else _survivors_only(units, c["lost"]), c["lost"], L)
+        assert unknown == c["unknown"], c
+        assert sorted(rec) == sorted(c["lost"]) == sorted(c["rec"]), c
+        for x, toks in c["rec"].items():
+            for o, tok in enumerate(toks):
+                known = bool(seg[x][o // 2])
+                assert known == (tok != "??"), (c, x, o)
+                if known:
+                    assert rec[x][o] == int(tok, 16), (c, x, o)
+
+
+def pin_collab_bruteforce(orc):
+    """Which segments are determined by what survives, by exhaustive search: shards of k-1
+    one-bit segments, every value of the lost shards tried against every surviving copy and unit
+    (the units recomputed with plain Python XOR from the segment map written as a table).  A
+    segment is recoverable iff all candidates that fit agree on it; the oracle must find exactly
+    those, with the right values, for every set of one, two or three lost members."""
+    import itertools
+    rng = np.random.default_rng(53)
+    for k in (3, 4, 5):
+        nseg = k - 1
+        table = [[None] * k for _ in range(k)]          # table[i][j]: segment of j covered on i
+        for j in range(k):
+            r = 0
+            for i in range(k):
+                if i != j:
+                    table[i][j] = r
+                    r += 1
+        truth = [rng.integers(0, 2, size=nseg, dtype=np.uint8) for _ in range(k)]
+
+        def unit_of(i, sh):
+            v = 0
+            for j in range(k):
+                if j != i:
+                    v ^= int(sh[j][table[i][j]])
+            return v
+        strategies = [([1], True), ([1], False), ([], True), ([1, 2], False), ([2], True)]
+        if k >= 4:
+            strategies.append(([1, 3], True))
+        for offs, aec in strategies:
+            offs = [d for d in offs if d < k]
+            dups, units = _holdings(orc, truth, offs, aec)
+            for nlost in (1, 2, 3):
+                if nlost >= k:
+                    continue
+                for lost in itertools.combinations(range(k), nlost):
+                    # exhaustive: all values of the lost shards that fit what survives
+                    fits = []
+                    for bits in itertools.product((0, 1), repeat=nlost * nseg):
+                        cand = [t.copy() for t in truth]
+                        for n, x in enumerate(lost):
+                            cand[x] = np.array(bits[n * nseg:(n + 1) * nseg], dtype=np.uint8)
+                        ok = True
+                        for d in offs:
+                            for i in range(k):
+                                if i not in lost and not np.array_equal(cand[(i + d) % k], truth[(i + d) % k]):
+                                    ok = False
+                        if aec:
+                            for i in range(k):
+                                if i not in lost and unit_of(i, cand) != unit_of(i, truth):
+                                    ok = False
+                        if ok:
+                            fits.append(cand)
+                    assert fits, "the truth itself must fit"
+                    rec, unknown, seg = orc.collab_recover(
+                        _survivors_only(truth, lost), [_survivors_only(d, lost) for d in dups], offs,
+                        None if units is None else _survivors_only(units, lost), lost, nseg)
+                    n_unknown = 0
+                    for x in lost:
+                        for r in range(nseg):
+                            determined = len({int(c[x][r]) for c in fits}) == 1
+                            assert bool(seg[x][r]) == determined, (k, offs, aec, lost, x, r)
+                            if determined:
+                                assert rec[x][r] == truth[x][r], (k, offs, aec, lost, x, r)
+                            else:
+                                n_unknown += 1
+                    assert unknown == n_unknown, (k, offs, aec, lost)
+
+
+def pin_collab_invariants(orc):
+    """Random bytes, ragged lengths: one loss is always recovered by either strategy alone; two
+    redundant copies with different offsets survive any two losses (k >= 3); a shard is never
+    rebuilt from its own lost holdings (they are poisoned)."""
+    import itertools
+    rng = np.random.default_rng(59)
+    for k in (3, 4, 6):
+        for L in (1, 7, 41, 1000):
+            shards = [_rand(rng, L) for _ in range(k)]
+            for offs, aec, max_lost in (([1], False, 1), ([], True, 1), ([1, 2], False, 2), ([2], True, 1)):
+                dups, units = _holdings(orc, shards, offs, aec)
+                for nlost in range(1, max_lost + 1):
+                    for lost in itertools.combinations(range(k), nlost):
+                        sh = [(_rand(rng, L) if i in lost else a) for i, a in enumerate(shards)]
+                        du = [[(_rand(rng, L) if i in lost else a) for i, a in enumerate(d)] for d in dups]
+                        un = None if units is None else \
+                            [(_rand(rng, a.size) if i in lost else a) for i, a in enumerate(units)]
+                        rec, unknown, seg = orc.collab_recover(sh, du, offs, un, lost, L)
+                        assert unknown == 0 and seg.all(), (k, L, offs, aec, lost)
+                        for x in lost:
+                            assert np.array_equal(rec[x], shards[x]), (k, L, offs, aec, lost, x)
+
+
 ALL_PINS = [pin_golden_xor, pin_golden_pack, pin_closed_form_parity, pin_closed_form_pack,
             pin_zero_sum, pin_round_trip_and_bucket_independence, pin_bruteforce_reconstruct,
             pin_special_cases, pin_linearity_and_word_width, pin_float_payloads, pin_padded,
-            pin_rejects, pin_golden_rotated, pin_rotated_invariants, pin_rotated_bruteforce]
+            pin_rejects, pin_golden_rotated, pin_rotated_invariants, pin_rotated_bruteforce,
+            pin_golden_collab, pin_collab_bruteforce, pin_collab_invariants]

@@ -47,8 +47,24 @@ MUTANTS = {
     # rotated placement: the other rotation (index by the protected shard, not by the member)
     "rotated_transposed": ("static uint32_t oracle_rot_index(uint32_t i, uint32_t j) { return i < j ? i : i - 1; }",
                            "static uint32_t oracle_rot_index(uint32_t i, uint32_t j) { return j < i ? j : j - 1; }"),
-    # rotated placement: the zero-extension of the last segment forgotten (reads past the shard)
+    # rotated decode: the protecting member's own shard is XORed in as well
     "rotated_decode_skips_member": ("if (j == i || j == lost) continue;", "if (j == lost) continue;"),
+    # rotated placement: the zero extension of the last segment forgotten (the bytes beyond the
+    # stream read as a repeat of its last byte instead of zero)
+    "rotated_no_zero_extension": ("            if (y < L) p ^= shards[j][y];",
+                                  "            if (L) p ^= shards[j][y < L ? y : L - 1];"),
+    # collaborative recovery: the copy of S_x looked for on the wrong side (x + d instead of x - d)
+    "collab_wrong_holder": ("const uint32_t holder = (x + k - arc_offsets[a]) % k;",
+                            "const uint32_t holder = (x + arc_offsets[a]) % k;"),
+    # collaborative recovery: a segment decoded although the unit covers another unknown segment
+    "collab_decodes_too_early": ("!seg_known[j * nseg + oracle_rot_index(i, j)]) ready = 0;",
+                                 "!seg_known[j * nseg + oracle_rot_index(i, j)]) ready = 1;"),
+    # collaborative recovery: the member that covers segment r taken to be member r
+    "collab_wrong_protector": ("const uint32_t i = r < x ? r : r + 1;               /* r(i, x) == r */",
+                               "const uint32_t i = r;"),
+    # collaborative recovery: a lost member's recovered bytes not used when decoding another
+    "collab_ignores_recovered": ("if (y < L) v ^= lost[j] ? out[j][y] : shards[j][y];",
+                                 "if (y < L) v ^= shards[j][y];"),
     # padded encode ignores the lengths
     "padded_ignores_len": ("p ^= (i < lens[s]) ? shards[s][i] : 0;",
                            "p ^= (i < lens[0]) ? shards[s][i < lens[s] ? i : 0] : 0;"),
