@@ -249,8 +249,8 @@ struct reft_plan {
     // bucket pipelines
     Event pack_filled[kGroups], pack_free[kGroups], pack_done, pack_begin, rest_begin;
     Event rest_filled[kGroups], rest_free[kGroups], rest_done, rest_copied;
-    // helper stream for the staged transport's piece copies (tunable "dma_streams"), created with
-    // the plan at the default priority, and the events that fork it from / join it to copy_stream
+    // helper stream for the staged transport's piece copies (tunable "dma_streams" = 2), default
+    // priority, and the events that fork it from / join it to copy_stream
     hipStream_t aux = nullptr;
     Event aux_fork, aux_join;
     // rotated parity placement: plans derived from this one (merged piece lists of shifted
@@ -632,8 +632,11 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
         (rc = make_event(p->rest_begin)) || (rc = make_event(p->aux_fork)) ||
         (rc = make_event(p->aux_join)))
         return rc;
-    // (a stream that never gets work occupies no hardware queue)
-    HIPCHK(hipStreamCreateWithFlags(&p->aux, hipStreamNonBlocking));
+    // The helper stream exists only where it is asked for: a stream takes its place among the
+    // process's few hardware queues when it is created, whether it ever gets work or not (two
+    // idle helper streams made here were enough to push a snapshot and a restore, on streams
+    // created after them, onto one queue, where they took turns on the link).
+    if (g_dma_streams.load() == 2) HIPCHK(hipStreamCreateWithFlags(&p->aux, hipStreamNonBlocking));
     // everything a data-moving call needs is made here: the pointer-table pool, the host scratch
     // for row tables, and the whole stream's piece lists for the staged transport
     p->ring_cap = (uint64_t)kRingRows * T;
@@ -824,16 +827,39 @@ static void classify_pieces(const reft_plan *p, uint64_t bucket_begin, uint64_t 
         for (uint64_t o = lo; o < hi;) {
             while (p->off[i + 1] <= o) ++i;              // o < hi <= L = off[T]
             const uint64_t pe = p->off[i + 1] < hi ? p->off[i + 1] : hi;
-            if (pe - o >= dma_min) {
+            // (a piece carried over from the previous bucket, see below, leaves now unless the
+            // bucket's first piece is the large rest of its span: a run never crosses a bucket)
+            if (o == lo && !pending.empty() &&
+                !(pe - o >= dma_min && pending.back().span == i &&
+                  pending.back().o + pending.back().n == o))
                 flush();
-                dmas.push_back(Dma{o, pe - o, i});
+            // A bucket boundary is no reason to split a copy that needs no staging: a piece that
+            // continues the previous copy's span is added to that copy, and a small first piece of
+            // a span is carried into the large one that follows it.
+            if (pending.empty() && !dmas.empty() && dmas.back().span == i &&
+                dmas.back().o + dmas.back().n == o && dmas.back().n >= dma_min) {
+                dmas.back().n += pe - o;
+            } else if (pe - o >= dma_min) {
+                uint64_t start = o;
+                if (!pending.empty() && pending.back().span == i &&
+                    pending.back().o + pending.back().n == o) {
+                    start = pending.back().o;
+                    pending.pop_back();
+                }
+                flush();
+                dmas.push_back(Dma{start, pe - start, i});
             } else {
                 pending.push_back(Dma{o, pe - o, i});
             }
             o = pe;
         }
-        flush();                                         // a run never crosses a bucket
+        // a run never crosses a bucket; a single small piece at the bucket's end may still be
+        // the head of a span that continues in the next bucket
+        if (pending.size() == 1 && b + 1 < bucket_end && p->off[pending.back().span + 1] > hi)
+            continue;
+        flush();
     }
+    flush();
 }
 
 // The piece lists of buckets [b0, b1) under the current tunables: made once per range and kept
@@ -944,6 +970,8 @@ static int issue_piece_copies(reft_plan *p, const std::vector<Dma> &dmas, hipStr
     int rc;
     const bool two = g_dma_streams.load() == 2 && dmas.size() >= 4;
     if (two) {
+        // made with the plan when "dma_streams" was 2 then, else on the first call that wants it
+        if (!p->aux) HIPCHK(hipStreamCreateWithFlags(&p->aux, hipStreamNonBlocking));
         if ((rc = record(p->aux_fork, cs))) return rc;
         if ((rc = wait_on(p->aux, p->aux_fork))) return rc;
     }
