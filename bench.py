@@ -4,27 +4,40 @@
 One *step* is one pass of the whole path over one rank-shaped synthetic state, inputs resident in
 HBM before the clock starts:
 
-  save   reft_snapshot_pack   own shard   -> pinned host   (staged transport: DMA copies straight
+  save   reft_parity_encode   k shards    -> parity (device)                  (k-way XOR, in place)
+         reft_snapshot_pack   own shard   -> pinned host   (staged transport: DMA copies straight
                                                             from the tensors, gather kernel only
                                                             for runs of small tensors)
-         reft_parity_encode   k shards    -> parity (device)                  (k-way XOR, in place)
          reft_snapshot_pack   parity      -> pinned host
-  load   reft_restore         host shard  -> fresh tensors  (staged transport as well; it starts as
-                                                             soon as the shard's snapshot has
-                                                             landed and shares the link with the
-                                                             parity's snapshot, full duplex)
+  load   reft_restore         host shard  -> fresh tensors  (staged transport as well)
          reft_restore         host parity -> device
          reft_reconstruct_spans  k-1 survivors + parity -> lost shard's tensors (k-way XOR)
+
+Consecutive steps are software-pipelined the way a trainer that checkpoints every iteration and a
+recovery that loads the last complete checkpoint would share the machine: the host link carries
+snapshots (device to host) and restores (host to device) at the same time.  Per step, in order on
+the save stream: [encode of step n, decode of step n-2] (the XOR window: it opens when the previous
+step's copies have ended, so nothing runs beside the two HBM-bound kernels), snapshot of the
+shard, snapshot of the parity; on the load stream:
+restore of the shard (beside the parity's snapshot), restore of the parity (beside the next step's
+shard snapshot).  Every dependency is an event: a host buffer is overwritten only after its
+restore has read it, the parity is restored only after the decode that read the previous one.
+The timed region holds exactly K encodes, 2 K snapshots, 2 K restores and K decodes; the
+pipeline fills and drains inside it.  ``--serial`` runs the steps one after the other instead.
 
 ``value`` is the step's checkpoint traffic, 4*L bytes (shard + parity saved to host, shard + parity
 loaded back), divided by the step time: the path is bound by the host link, which is why the
 HBM-bound kernels are reported separately under ``stages`` and ``roofline``.
 
-The last line printed is the JSON record.  ``python bench.py --help`` lists the options.
+The record's headline is the configuration the metric's "concurrent step slowdown" is defined on
+(3: 34B-shaped, 8 x 15 GB); ``per_config`` holds a shorter run of the other Llama-shaped
+configurations.  The last line printed is the JSON record.  ``python bench.py --help`` lists the
+options.
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -36,43 +49,53 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E, published
 LINK_PEAK_GBPS = 63.0            # PCIe Gen5 x16, one direction: 32 GT/s * 16 * 128/130 / 8
+LINK_DUPLEX_PEAK_GBPS = 2 * LINK_PEAK_GBPS
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def main() -> int:
+def pct(x, peak):
+    return round(100.0 * x / peak, 1)
+
+
+def parse_args():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawTextHelpFormatter)
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=1, help="workload configuration 0..4 (default 1)")
+    ap.add_argument("--config", type=int, default=3, help="workload configuration 0..4 (default 3)")
+    ap.add_argument("--per-config", type=str, default="1,2,4",
+                    help="configurations that get a shorter run of their own under per_config "
+                         "(comma separated; '' = none)")
+    ap.add_argument("--per-config-steps", type=int, default=6)
+    ap.add_argument("--serial", action="store_true",
+                    help="no pipelining across steps: a step's save starts when the previous "
+                         "step's load has ended")
+    ap.add_argument("--queue-depth", type=int, default=1, choices=[1, 2, 3],
+                    help="before queuing a step the host waits for the parity snapshot of the step "
+                         "this many steps back (default 1).  A trainer takes one snapshot per "
+                         "iteration; with two or three steps' copies queued ahead (some 4000 "
+                         "hipMemcpyAsync calls) the runtime's device-to-host copies drop to a "
+                         "quarter of their rate")
+    ap.add_argument("--trace-phases", action="store_true",
+                    help="log when each phase of each timed step began and ended (HIP events)")
     ap.add_argument("--gemm-seconds", type=float, default=0.0,
                     help="length of the bf16 GEMM proxy loop for the slowdown figure "
                          "(0 = as long as one save phase; negative = skip)")
     ap.add_argument("--snapshot-wgs", type=int, default=0,
                     help="cap on workgroups of the snapshot kernels while the GEMM proxy runs")
     ap.add_argument("--save-path", choices=["direct", "staged"], default="staged",
-                    help="snapshot transport. staged: staging ring + hipMemcpyAsync on the DMA "
-                         "engines (what runs beside training); direct: the gather kernel stores "
-                         "to pinned host memory itself")
+                    help="snapshot transport. staged: hipMemcpyAsync on the DMA engines (what runs "
+                         "beside training); direct: the gather kernel stores to pinned host memory")
     ap.add_argument("--load-path", choices=["direct", "staged"], default="staged",
                     help="restore transport. staged (default): runtime copies, which share the link "
-                         "well with the parity snapshot going the other way; direct: the scatter "
-                         "kernel reads pinned host memory itself (fastest when nothing else runs)")
-    ap.add_argument("--no-overlap-load", action="store_true",
-                    help="start the load phase only when the whole save phase has landed (default: "
-                         "the own shard's restore starts as soon as its snapshot is on the host, "
-                         "beside the parity's snapshot, which uses the link's other direction)")
+                         "well with a snapshot going the other way; direct: the scatter kernel "
+                         "reads pinned host memory itself (fastest when nothing else runs)")
     ap.add_argument("--dma-streams", type=int, default=0, choices=[0, 1, 2],
                     help="staged transport: 2 = piece copies alternate with a helper stream "
                          "(0 = library default)")
-    ap.add_argument("--one-stream-save", action="store_true",
-                    help="staged save: gather kernels and copies in order on one stream")
-    ap.add_argument("--two-stream-load", action="store_true",
-                    help="staged load: copies and scatter kernels on two streams (default: in order "
-                         "on one, which keeps the process within its four hardware queues)")
     ap.add_argument("--staging-mib", type=int, default=1024,
                     help="size of each staging ring in MiB (split into bucket-sized slots)")
     ap.add_argument("--link-wgs", type=int, default=0,
@@ -80,8 +103,6 @@ def main() -> int:
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device-to-device copy of 1 GiB (torch), the kernel of "
                          "known size that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
-    ap.add_argument("--overlap-encode", action="store_true",
-                    help="start the own shard's snapshot first and run the parity encode beside it")
     ap.add_argument("--graph-copies", type=int, default=-1, choices=[-1, 0, 1, 2],
                     help="tunable graph_copies: staged piece copies as a replayed hipGraph "
                          "(0 off, 1 independent nodes, 2 chain)")
@@ -93,6 +114,7 @@ def main() -> int:
     ap.add_argument("--burst-stage", type=int, default=0, help="tunable burst_stage_bytes")
     ap.add_argument("--burst-wgs", type=int, default=0, help="tunable burst_wgs_per_cu")
     ap.add_argument("--no-stages", action="store_true", help="skip the per-stage measurements")
+    ap.add_argument("--stage-reps", type=int, default=20)
     ap.add_argument("--has-demo", action="store_true",
                     help="instead of the benchmark: run a synthetic pipeline-stage timeline (idle "
                          "bubble, then a GEMM burst) with no snapshot, with the whole save phase "
@@ -105,8 +127,468 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-mib", type=int, default=2048,
                     help="bytes per shard of the CPU-oracle sample, MiB")
-    args = ap.parse_args()
+    return ap.parse_args()
 
+
+class Bench:
+    """One configuration resident on the GPU: state, plans, buffers, streams, and the step."""
+
+    def __init__(self, args, cfg, torch, reft, pinned, streams):
+        from workload import fill_shard, make_workload, span_nbytes
+
+        self.args, self.torch, self.reft = args, torch, reft
+        self.dev = dev = torch.device("cuda:0")
+        # two streams carry a step: s_save the XOR kernels and the snapshots, s_load the restores
+        self.s_save, self.s_load = streams
+        self.wl = wl = make_workload(cfg)
+        self.k, self.L, self.T = wl.k, wl.L, len(wl.spans)
+        k, L = self.k, self.L
+        self.lost = wl.lost
+        self.own = (wl.lost + 1) % k
+        log(f"[bench] config {wl.cfg}: {wl.description}; k={k} T={self.T} L={L} "
+            f"buckets={len(wl.bucket_nbytes)} lost={self.lost} own={self.own}")
+        t0 = time.time()
+        self.shards = [fill_shard(wl, s, dev) for s in range(k)]
+        torch.cuda.synchronize()
+        log(f"[bench] generated {k * L / 1e9:.1f} GB of state in {time.time() - t0:.1f} s")
+
+        self.plan = reft.reft_plan_create(span_nbytes(wl), wl.bucket_nbytes)
+        bucket = reft.reft_plan_max_bucket_bytes(self.plan)
+        self.pplan = reft.reft_plan_create([L], None, bucket)      # the parity as a 1-span shard
+        self.save_staged = args.save_path == "staged"
+        self.load_staged = args.load_path == "staged"
+
+        def ring(p, use):
+            if not use:
+                return None
+            slot = reft.reft_plan_staging_slot_bytes(p)
+            nslots = max(2, min(64, (args.staging_mib << 20) // slot))
+            return torch.empty(nslots * slot, dtype=torch.uint8, device=dev)
+        # the staged transport needs its ring only for runs of small pieces
+        self.gathers, self.copies = reft.reft_plan_staged_work(self.plan)
+        self.stag_save = ring(self.plan, self.save_staged)
+        self.stag_psave = ring(self.pplan, self.save_staged)
+        self.stag_load = ring(self.plan, self.load_staged)
+        self.stag_pload = ring(self.pplan, self.load_staged)
+        self.host_snap, self.host_par = pinned[0][:L], pinned[1][:L]
+        self.parity = torch.empty(L, dtype=torch.uint8, device=dev)
+        self.parity2 = torch.empty(L, dtype=torch.uint8, device=dev)
+        self.fresh_own = [torch.empty_like(t) for t in self.shards[self.own]]
+        self.fresh_lost = [torch.empty_like(t) for t in self.shards[self.lost]]
+
+        sh = self.shards
+        self.p_own = reft.ptr_array(sh[self.own])
+        self.p_all = reft.ptr_array([t for s in sh for t in s])
+        self.p_surv = reft.ptr_array([None if s == self.lost else t for s, x in enumerate(sh) for t in x])
+        self.p_fresh_own = reft.ptr_array(self.fresh_own)
+        self.p_fresh_lost = reft.ptr_array(self.fresh_lost)
+        self.p_par = reft.ptr_array([self.parity])
+        self.p_par2 = reft.ptr_array([self.parity2])
+
+        # A staged snapshot that gathers runs of small pieces puts those kernels on a stream of
+        # their own (s_pack); the Llama-shaped configurations have no such runs, and one stream
+        # serves as pack_stream and copy_stream (a hardware queue less).
+        self.s_pack = torch.cuda.Stream() if (self.save_staged and self.gathers) else self.s_save
+        self.enc_events, self.dec_events = [], []
+        self.phases, self.tracing = [], False
+        self.reset_pipeline()
+
+    # ---- the step ---------------------------------------------------------------------------------
+    # Buffers and who touches them: parity (encode writes, parity snapshot reads; both on s_save),
+    # host_snap (shard snapshot writes, shard restore reads), host_par (parity snapshot writes,
+    # parity restore reads), parity2 (parity restore writes, decode reads).  ev[name][n] is recorded
+    # behind the named operation of step n.
+    def reset_pipeline(self):
+        self.n = 0
+        self.ev = {name: {} for name in ("shard_saved", "par_saved", "shard_restored",
+                                         "par_restored", "decoded")}
+
+    def _mark(self, name, n, stream):
+        e = self.torch.cuda.Event()
+        e.record(stream)
+        self.ev[name][n] = e
+        self.ev[name].pop(n - 4, None)
+
+    def _wait(self, stream, name, n):
+        e = self.ev[name].get(n)
+        if e is not None:
+            stream.wait_event(e)
+
+    def _phase(self, name, n, stream, fn):
+        """Run fn; with --trace-phases, bracket it with timing events on its stream."""
+        if not (self.args.trace_phases and self.tracing):
+            fn()
+            return
+        torch = self.torch
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        fn()
+        e1.record(stream)
+        self.phases.append((name, n, e0, e1))
+
+    def _timed(self, timed, store, fn):
+        if not timed:
+            fn()
+            return
+        torch = self.torch
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(self.s_save)
+        fn()
+        e1.record(self.s_save)
+        store.append((e0, e1))
+
+    def _encode(self, n, timed):
+        self._timed(timed, self.enc_events, lambda: self.reft.reft_parity_encode(
+            self.plan, self.p_all, self.k, self.parity, self.s_save))
+
+    def _decode(self, n, timed):
+        self._wait(self.s_save, "par_restored", n)
+        self._timed(timed, self.dec_events, lambda: self.reft.reft_reconstruct_spans(
+            self.plan, self.p_surv, self.k, self.lost, self.parity2, self.p_fresh_lost, self.s_save))
+        self._mark("decoded", n, self.s_save)
+
+    def _snapshot_shard(self, n):
+        self._wait(self.s_save, "shard_restored", n - 1)          # host_snap has been read
+        if self.s_pack is not self.s_save:
+            self.s_pack.wait_stream(self.s_save)
+        self._phase("snapshot_shard", n, self.s_save, lambda: self.reft.reft_snapshot_pack(
+            self.plan, self.p_own, self.stag_save, self.host_snap, self.s_pack, self.s_save))
+        self._mark("shard_saved", n, self.s_save)
+
+    def _snapshot_parity(self, n):
+        self._wait(self.s_save, "par_restored", n - 1)            # host_par has been read
+        if self.s_pack is not self.s_save:
+            self.s_pack.wait_stream(self.s_save)                  # the encode produced the parity
+        self._phase("snapshot_parity", n, self.s_save, lambda: self.reft.reft_snapshot_pack(
+            self.pplan, self.p_par, self.stag_psave, self.host_par, self.s_pack, self.s_save))
+        self._mark("par_saved", n, self.s_save)
+
+    def _restore_shard(self, n):
+        self._wait(self.s_load, "shard_saved", n)
+        self._phase("restore_shard", n, self.s_load, lambda: self.reft.reft_restore(
+            self.plan, self.host_snap, self.stag_load, self.p_fresh_own, self.s_load, self.s_load))
+        self._mark("shard_restored", n, self.s_load)
+
+    def _restore_parity(self, n):
+        self._wait(self.s_load, "par_saved", n)
+        self._wait(self.s_load, "decoded", n - 1)                 # parity2 has been read
+        self._phase("restore_parity", n, self.s_load, lambda: self.reft.reft_restore(
+            self.pplan, self.host_par, self.stag_pload, self.p_par2, self.s_load, self.s_load))
+        self._mark("par_restored", n, self.s_load)
+
+    def step(self, timed=False):
+        n = self.n
+        # host-side pacing (see --queue-depth)
+        old = self.ev["par_saved"].get(n - self.args.queue_depth)
+        if old is not None:
+            old.synchronize()
+        # The XOR window opens when the previous step's shard restore has ended (the next snapshot
+        # needs its host buffer read anyway): DMA writes trickling into HBM beside the XOR kernels
+        # cost them 5 % (measured), and nothing else is in flight at this point.
+        self._wait(self.s_save, "shard_restored", n - 1)
+        self._encode(n, timed)
+        if self.args.serial:
+            self._snapshot_shard(n)
+            self._snapshot_parity(n)
+            self._restore_shard(n)                  # beside the parity's snapshot
+            self._restore_parity(n)
+            self._decode(n, timed)
+        else:
+            if n >= 2:
+                self._decode(n - 2, timed)          # the XOR window: encode(n), decode(n-2)
+            if n >= 1:
+                self._restore_parity(n - 1)         # beside this step's shard snapshot
+            self._snapshot_shard(n)
+            self._snapshot_parity(n)
+            self._restore_shard(n)                  # beside this step's parity snapshot
+        self.n = n + 1
+
+    def drain(self, timed=False):
+        """Queue what the pipeline still owes after the last step."""
+        n = self.n
+        if not self.args.serial and n >= 1:
+            if n >= 2:
+                self._decode(n - 2, timed)
+            self._restore_parity(n - 1)
+            self._decode(n - 1, timed)
+        self.reset_pipeline()
+
+    def save_phase(self):
+        """The save half alone (what runs beside training): encode, shard snapshot, parity snapshot."""
+        self._encode(0, False)
+        self._snapshot_shard(0)
+        self._snapshot_parity(0)
+        self.reset_pipeline()
+
+    def verified(self):
+        torch = self.torch
+        return all(torch.equal(a, b) for a, b in zip(self.fresh_own, self.shards[self.own])) and \
+            all(torch.equal(a, b) for a, b in zip(self.fresh_lost, self.shards[self.lost]))
+
+    def close(self):
+        self.reft.reft_plan_destroy(self.plan)
+        self.reft.reft_plan_destroy(self.pplan)
+
+
+# --------------------------------------------------------------------------------------------------
+# measurements on one configuration
+# --------------------------------------------------------------------------------------------------
+def run_steps(b, steps, warmup):
+    torch = b.torch
+    for _ in range(warmup):
+        b.step()
+    b.drain()
+    torch.cuda.synchronize()
+    # poison the outputs so that the check below sees this run's results
+    for t in b.fresh_own + b.fresh_lost:
+        t.view(torch.uint8).fill_(0x5A)
+    torch.cuda.synchronize()
+    b.enc_events.clear()
+    b.dec_events.clear()
+    b.tracing = True
+    base = torch.cuda.Event(enable_timing=True)
+    base.record(b.s_save)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        b.step(timed=True)
+    b.drain(timed=True)
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t0
+    b.tracing = False
+    if b.args.trace_phases:
+        rows = [(base.elapsed_time(e0), base.elapsed_time(e1), name, n) for name, n, e0, e1 in b.phases]
+        rows += [(base.elapsed_time(x), base.elapsed_time(y), "encode", i) for i, (x, y) in enumerate(b.enc_events)]
+        rows += [(base.elapsed_time(x), base.elapsed_time(y), "decode", i) for i, (x, y) in enumerate(b.dec_events)]
+        for t_a, t_b, name, n in sorted(rows):
+            log(f"[phase] {t_a:9.1f} .. {t_b:9.1f} ms  ({t_b - t_a:7.1f})  {name}({n})")
+        b.phases.clear()
+    ok = b.verified()
+    if not ok:
+        log("[bench] ERROR: restored or reconstructed tensors differ from the originals")
+    enc_ms = sum(x.elapsed_time(y) for x, y in b.enc_events) / len(b.enc_events)
+    dec_ms = sum(x.elapsed_time(y) for x, y in b.dec_events) / len(b.dec_events)
+    assert len(b.enc_events) == steps and len(b.dec_events) == steps
+    return t_total / steps, enc_ms, dec_ms, ok
+
+
+def measure_stages(b, reps):
+    torch, reft = b.torch, b.reft
+    k, L, dev, plan, pplan = b.k, b.L, b.dev, b.plan, b.pplan
+    s = b.s_save
+
+    def timed_alone(fn, stream, reps=reps, warm=3):
+        """Median of `reps` timed repetitions after `warm` untimed ones."""
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e-3)
+        ts.sort()
+        return ts[len(ts) // 2]
+
+    packed = torch.empty(L, dtype=torch.uint8, device=dev)
+    t_pack = timed_alone(lambda: reft.reft_pack_device(plan, b.p_own, packed, s), s)
+    t_unpack = timed_alone(lambda: reft.reft_unpack_device(plan, packed, b.p_fresh_own, s), s)
+    # the 1:1 ceiling the two are held against: the same kernel as a plain copy of one span of L
+    # bytes (16-byte vectors, nothing ragged), and the runtime's own device copy for scale
+    t_copy = timed_alone(lambda: reft.reft_pack_device(pplan, b.p_par, packed, s), s)
+    with torch.cuda.stream(s):
+        t_blit = timed_alone(lambda: packed.copy_(b.parity), s, reps=min(reps, 7))
+    t_enc = timed_alone(lambda: reft.reft_parity_encode(plan, b.p_all, k, b.parity, s), s)
+    burst = dict(zip(("rounds_met", "rounds_timed_out", "rounds_not_waited", "group_completions"),
+                     reft.reft_plan_burst_stats(plan)))
+    t_rec = timed_alone(lambda: reft.reft_reconstruct_spans(plan, b.p_surv, k, b.lost, b.parity2,
+                                                            b.p_fresh_lost, s), s)
+    del packed
+    # the paper's rotated placement: all k members' units, then the decode of the lost member
+    Lseg = reft.reft_segment_bytes(plan, k)
+    units = [torch.empty(Lseg, dtype=torch.uint8, device=dev) for _ in range(k)]
+    p_units = reft.ptr_array(units)
+
+    def all_units():
+        for i in range(k):
+            reft.reft_parity_encode_rotated(plan, b.p_all, k, i, units[i], s)
+    t_rot = timed_alone(all_units, s, reps=min(reps, 10))
+    t_rotdec = timed_alone(lambda: reft.reft_reconstruct_rotated(plan, b.p_all, p_units, k, b.lost,
+                                                                 b.p_fresh_lost, s), s, reps=min(reps, 10))
+    rot_ok = all(torch.equal(x, y) for x, y in zip(b.fresh_lost, b.shards[b.lost]))
+    del units
+
+    def snap():
+        reft.reft_snapshot_pack(plan, b.p_own, b.stag_save, b.host_snap, b.s_pack, s)
+        if b.s_pack is not s:
+            s.wait_stream(b.s_pack)
+
+    def rest():
+        reft.reft_restore(plan, b.host_snap, b.stag_load, b.p_fresh_own, s, s)
+
+    def both():                                     # the two directions of the link at once
+        b.s_load.wait_stream(s)                     # the restore starts with the timed region
+        reft.reft_snapshot_pack(pplan, b.p_par, b.stag_psave, b.host_par, b.s_pack, s)
+        reft.reft_restore(plan, b.host_snap, b.stag_load, b.p_fresh_own, b.s_load, b.s_load)
+        s.wait_stream(b.s_load)
+    t_snap = timed_alone(snap, s, reps=5, warm=1)
+    t_rest = timed_alone(rest, s, reps=5, warm=1)
+    t_both = timed_alone(both, s, reps=5, warm=1)
+
+    stages = {
+        "pack_kernel_GBps": round(2 * L / t_pack / 1e9, 1),
+        "unpack_kernel_GBps": round(2 * L / t_unpack / 1e9, 1),
+        "copy_ceiling_GBps": round(2 * L / t_copy / 1e9, 1),
+        "runtime_copy_GBps": round(2 * L / t_blit / 1e9, 1),
+        "parity_encode_GBps": round((k + 1) * L / t_enc / 1e9, 1),
+        "reconstruct_GBps": round((k + 1) * L / t_rec / 1e9, 1),
+        "rotated_units_GBps": round(k * k * Lseg / t_rot / 1e9, 1),
+        "rotated_decode_GBps": round(k * (k - 1) * Lseg / t_rotdec / 1e9, 1),
+        "rotated_decode_verified": bool(rot_ok),
+        "snapshot_d2h_GBps": round(L / t_snap / 1e9, 2),
+        "restore_h2d_GBps": round(L / t_rest / 1e9, 2),
+        "duplex_GBps": round(2 * L / t_both / 1e9, 2),
+        "encode_burst_rounds": burst,
+        "note": "copy_ceiling = the gather kernel as a plain copy of L bytes in one span (the 1:1 "
+                "streaming ceiling of this part for hand-written 16-byte-vector code); duplex = one "
+                "snapshot and one restore of L bytes each at the same time, both directions summed",
+    }
+    stages["pct_hbm_peak"] = {n: pct(stages[n], HBM_PEAK_GBPS) for n in
+                              ("pack_kernel_GBps", "unpack_kernel_GBps", "copy_ceiling_GBps",
+                               "parity_encode_GBps", "reconstruct_GBps", "rotated_units_GBps",
+                               "rotated_decode_GBps")}
+    stages["pct_link_peak"] = {"snapshot_d2h_GBps": pct(stages["snapshot_d2h_GBps"], LINK_PEAK_GBPS),
+                               "restore_h2d_GBps": pct(stages["restore_h2d_GBps"], LINK_PEAK_GBPS),
+                               "duplex_GBps": pct(stages["duplex_GBps"], LINK_DUPLEX_PEAK_GBPS)}
+    return stages
+
+
+def gemm_proxy(b):
+    """bf16 8192^3 GEMMs on the current stream, alone and beside one save phase."""
+    torch, reft, args = b.torch, b.reft, b.args
+    n = 8192
+    A = torch.randn(n, n, device=b.dev, dtype=torch.bfloat16)
+    B = torch.randn(n, n, device=b.dev, dtype=torch.bfloat16)
+    C = torch.empty(n, n, device=b.dev, dtype=torch.bfloat16)
+    cur = torch.cuda.current_stream()
+
+    def gemms(count):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(cur)
+        for _ in range(count):
+            torch.matmul(A, B, out=C)
+        e1.record(cur)
+        return e0, e1
+
+    e0, e1 = gemms(20)
+    torch.cuda.synchronize()
+    e0, e1 = gemms(50)
+    torch.cuda.synchronize()
+    t_one = e0.elapsed_time(e1) * 1e-3 / 50
+    t_save = 1e9
+    for _ in range(2):                                   # the save phase alone
+        torch.cuda.synchronize()
+        ts0 = time.perf_counter()
+        b.save_phase()
+        torch.cuda.synchronize()
+        t_save = min(t_save, time.perf_counter() - ts0)
+    span = args.gemm_seconds if args.gemm_seconds > 0 else t_save
+    count = max(10, int(span / t_one))
+    e0, e1 = gemms(count)
+    torch.cuda.synchronize()
+    t_alone = e0.elapsed_time(e1) * 1e-3
+    if args.snapshot_wgs:
+        reft.reft_set_tunable("max_wgs", args.snapshot_wgs)
+    torch.cuda.synchronize()
+    ts0 = time.perf_counter()
+    b.save_phase()
+    e0, e1 = gemms(count)
+    e1.synchronize()
+    t_with = e0.elapsed_time(e1) * 1e-3
+    torch.cuda.synchronize()
+    t_save_with = time.perf_counter() - ts0
+    reft.reft_set_tunable("max_wgs", 0)
+    return {
+        "gemm": "bf16 8192x8192x8192 (torch.matmul as the load)",
+        "gemms": count,
+        "tflops_alone": round(2 * n ** 3 * count / t_alone / 1e12, 1),
+        "t_alone_s": round(t_alone, 4),
+        "t_with_snapshot_s": round(t_with, 4),
+        "slowdown_pct": round(100.0 * (t_with - t_alone) / t_alone, 2),
+        "save_phase_alone_s": round(t_save, 4),
+        "save_phase_with_gemm_s": round(t_save_with, 4),
+        "snapshot_wgs": args.snapshot_wgs,
+    }
+
+
+def run_config(args, cfg, torch, reft, pinned, streams, primary):
+    """All measurements of one configuration; returns its part of the record."""
+    b = Bench(args, cfg, torch, reft, pinned, streams)
+    k, L = b.k, b.L
+    try:
+        if args.has_demo:
+            return has_demo(b)
+        if args.calibration_copy and primary:
+            x = torch.empty(1 << 30, dtype=torch.uint8, device=b.dev).fill_(7)
+            y = torch.empty(1 << 30, dtype=torch.uint8, device=b.dev)
+            y.copy_(x)
+            torch.cuda.synchronize()
+            del x, y
+        steps = args.steps if primary else args.per_config_steps
+        warmup = args.warmup if primary else 1
+        t_step, enc_ms, dec_ms, ok = run_steps(b, steps, warmup)
+        value = 4 * L / t_step / 1e9
+        enc_gbps = (k + 1) * L / (enc_ms * 1e-3) / 1e9
+        dec_gbps = (k + 1) * L / (dec_ms * 1e-3) / 1e9
+        burst_on = reft.reft_get_tunable("burst") and k >= reft.reft_get_tunable("burst_min_rows")
+        traffic, source = measured_traffic(b.wl.cfg)
+        out = {
+            "workload": f"config {b.wl.cfg}: {b.wl.description}",
+            "k": k, "spans": b.T, "stream_bytes": L, "buckets": len(b.wl.bucket_nbytes),
+            "staged_snapshot": {"gather_launches": b.gathers, "copies": b.copies},
+            "steps": steps, "warmup": warmup,
+            "ms_per_step": round(t_step * 1e3, 2),
+            "value_GBps": round(value, 2),
+            "pct_link_duplex_peak": pct(value, LINK_DUPLEX_PEAK_GBPS),
+            "verified": bool(ok),
+            "roofline": {
+                "kernel": (f"k_gather_burst<{k}>" if burst_on else f"k_gather<{k}>") +
+                          f" (parity encode over {k} span tables)",
+                "bound": "hbm",
+                "achieved": round(enc_gbps, 1),
+                "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s",
+                "frac": round(enc_gbps / HBM_PEAK_GBPS, 4),
+                "traffic": traffic,
+                "traffic_source": source,
+                "bytes_per_launch": (k + 1) * L,
+                "avg_launch_ms": round(enc_ms, 3),
+                "reconstruct_achieved": round(dec_gbps, 1),
+                "reconstruct_frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
+                "reconstruct_avg_launch_ms": round(dec_ms, 3),
+            },
+        }
+        if not args.no_stages:
+            out["stages"] = measure_stages(b, args.stage_reps if primary else min(args.stage_reps, 7))
+        if args.gemm_seconds >= 0:
+            out["gemm_proxy"] = gemm_proxy(b)
+        if primary and b.save_staged and not args.no_has and args.gemm_seconds >= 0:
+            out["stage_timeline"] = has_demo(b, iterations=3)
+        if primary and not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline(b.wl, b.shards, b.own, b.lost, args.cpu_sample_mib << 20)
+        return out
+    finally:
+        b.close()
+        del b
+        gc.collect()
+        torch.cuda.empty_cache()
+
+
+def main() -> int:
+    args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU (the simulated node's k shards live in one "
               "GPU's HBM); --gpus N with N > 1 is not supported.", file=sys.stderr)
@@ -115,53 +597,20 @@ def main() -> int:
     import torch
 
     import paper_2310_12670_amd as reft
-    from workload import fill_shard, make_workload, span_nbytes
+    from workload import make_workload
 
     assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU path)"
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    wl = make_workload(args.config)
-    k, L, T = wl.k, wl.L, len(wl.spans)
-    sizes = span_nbytes(wl)
-    lost = wl.lost
-    own = (lost + 1) % k
-    log(f"[bench] config {wl.cfg}: {wl.description}; k={k} T={T} L={L} buckets={len(wl.bucket_nbytes)} "
-        f"lost={lost} own={own}")
-
-    t0 = time.time()
-    shards = [fill_shard(wl, s, dev) for s in range(k)]
+    torch.cuda.set_device(torch.device("cuda:0"))
+    # The step's two streams are made before anything else that makes streams: the runtime deals
+    # streams onto its few hardware queues (4 per process here) as they are created, and two
+    # streams on one queue take turns, which would cost the step its full-duplex use of the link.
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    for st in streams:
+        with torch.cuda.stream(st):
+            torch.zeros(1, device="cuda:0")
     torch.cuda.synchronize()
-    log(f"[bench] generated {k * L / 1e9:.1f} GB of state in {time.time() - t0:.1f} s")
-
-    plan = reft.reft_plan_create(sizes, wl.bucket_nbytes)
-    bucket = reft.reft_plan_max_bucket_bytes(plan)
-    pplan = reft.reft_plan_create([L], None, bucket)           # the parity as a 1-span shard
-    save_staged = args.save_path == "staged"
-    load_staged = args.load_path == "staged"
-    def ring(p, use):
-        if not use:
-            return None
-        slot = reft.reft_plan_staging_slot_bytes(p)
-        nslots = max(2, min(64, (args.staging_mib << 20) // slot))
-        return torch.empty(nslots * slot, dtype=torch.uint8, device=dev)
-    stag_save, stag_psave = ring(plan, save_staged), ring(pplan, save_staged)
-    stag_load, stag_pload = ring(plan, load_staged), ring(pplan, load_staged)
-    t0 = time.time()
-    host_snap = torch.empty(L, dtype=torch.uint8, pin_memory=True)
-    host_par = torch.empty(L, dtype=torch.uint8, pin_memory=True)
-    log(f"[bench] pinned {2 * L / 1e9:.1f} GB of host memory in {time.time() - t0:.1f} s")
-    parity = torch.empty(L, dtype=torch.uint8, device=dev)
-    parity2 = torch.empty(L, dtype=torch.uint8, device=dev)
-    fresh_own = [torch.empty_like(t) for t in shards[own]]
-    fresh_lost = [torch.empty_like(t) for t in shards[lost]]
-
-    p_own = reft.ptr_array(shards[own])
-    p_all = reft.ptr_array([t for sh in shards for t in sh])
-    p_surv = reft.ptr_array([None if s == lost else t for s, sh in enumerate(shards) for t in sh])
-    p_fresh_own = reft.ptr_array(fresh_own)
-    p_fresh_lost = reft.ptr_array(fresh_lost)
-    p_par = reft.ptr_array([parity])
-    p_par2 = reft.ptr_array([parity2])
+    others = [] if args.has_demo else \
+        [int(c) for c in args.per_config.split(",") if c.strip() and int(c) != args.config]
 
     if args.link_wgs:
         reft.reft_set_tunable("link_wgs", args.link_wgs)
@@ -179,322 +628,67 @@ def main() -> int:
         reft.reft_set_tunable("burst_stage_bytes", args.burst_stage)
     if args.burst_wgs:
         reft.reft_set_tunable("burst_wgs_per_cu", args.burst_wgs)
-    # s_snap / s_load carry the link-bound work (and, staged, the gather / scatter kernels);
-    # s_copy / s_h2d carry the DMA transfers of the staged path; s_xor the HBM-bound XOR kernels.
-    s_snap, s_xor, s_load = (torch.cuda.Stream() for _ in range(3))
-    s_copy = torch.cuda.Stream() if save_staged and not args.one_stream_save else s_snap
-    s_h2d = torch.cuda.Stream() if load_staged and args.two_stream_load else s_load
-    snap_done_stream = s_copy
-    enc_events, rec_events = [], []
-    # The runtime maps streams to its few hardware queues in the order in which they first get
-    # work; two streams on one queue run in turn.  Touch them in an order that keeps the two copy
-    # directions and the XOR kernels apart.
-    for st in (s_snap, s_copy, s_xor, s_load, s_h2d):
-        with torch.cuda.stream(st):
-            torch.zeros(1, device=dev)
-    torch.cuda.synchronize()
 
-    def save_phase(timed):
-        """Parity encode, then the snapshot of the own shard, then the parity's snapshot.
-        Returns the event after which the own shard's host copy is complete.  The encode runs
-        before the copies start (16 ms during which the link idles): beside copy traffic that
-        the runtime executes as kernels, as it does under rocprofv3, the write-burst kernel is
-        several times slower, and a trainer would place the encode in a bubble anyway.
-        --overlap-encode starts the own shard's snapshot first and the encode beside it."""
-        if args.overlap_encode:
-            reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_snap, s_copy)
-            own_done = torch.cuda.Event()
-            own_done.record(snap_done_stream)
-        if timed:
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(s_xor)
-        reft.reft_parity_encode(plan, p_all, k, parity, s_xor)
-        if timed:
-            e1.record(s_xor)
-            enc_events.append((e0, e1))
-        s_snap.wait_stream(s_xor)
-        if not args.overlap_encode:
-            reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_snap, s_copy)
-            own_done = torch.cuda.Event()
-            own_done.record(snap_done_stream)
-        reft.reft_snapshot_pack(pplan, p_par, stag_psave, host_par, s_snap, s_copy)
-        return own_done
+    # one pair of pinned host buffers serves every configuration (the box pins a limited amount)
+    t0 = time.time()
+    Lmax = max(make_workload(c).L for c in [args.config] + others)
+    pinned = [torch.empty(Lmax, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
+    log(f"[bench] pinned {2 * Lmax / 1e9:.1f} GB of host memory in {time.time() - t0:.1f} s")
 
-    def load_phase(timed, own_done):
-        """Restore of the own shard (as soon as its snapshot is complete: it shares the link with
-        the parity's snapshot, in the other direction), then the parity, then the decode."""
-        first = s_h2d
-        if not args.no_overlap_load:
-            first.wait_event(own_done)
-        else:
-            first.wait_stream(snap_done_stream)
-        reft.reft_restore(plan, host_snap, stag_load, p_fresh_own, s_h2d, s_load)
-        first.wait_stream(snap_done_stream)             # the parity is complete on the host
-        reft.reft_restore(pplan, host_par, stag_pload, p_par2, s_h2d, s_load)
-        s_xor.wait_stream(s_load)
-        if timed:
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(s_xor)
-        reft.reft_reconstruct_spans(plan, p_surv, k, lost, parity2, p_fresh_lost, s_xor)
-        if timed:
-            e1.record(s_xor)
-            rec_events.append((e0, e1))
-        # the next step's save may not overwrite what this step's load still reads
-        s_snap.wait_stream(s_xor)
-        s_snap.wait_stream(s_load)
-
+    main_rec = run_config(args, args.config, torch, reft, pinned, streams, primary=True)
     if args.has_demo:
-        rec = has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, host_snap,
-                       host_par, stag_save, stag_psave, s_snap, s_copy, s_xor)
-        reft.reft_plan_destroy(plan)
-        reft.reft_plan_destroy(pplan)
-        print(json.dumps(rec), flush=True)
+        print(json.dumps(main_rec), flush=True)
         return 0
+    per = {}
+    for c in others:
+        per[f"config{c}"] = run_config(args, c, torch, reft, pinned, streams, primary=False)
 
-    in_flight = []
-
-    def step(timed=False):
-        # Host-side pacing: at most two steps queued at once (a trainer takes one snapshot per
-        # iteration; thousands of queued copies and events only slow the runtime down).
-        if len(in_flight) >= 2:
-            in_flight.pop(0).synchronize()
-        load_phase(timed, save_phase(timed))
-        done = torch.cuda.Event()
-        done.record(s_xor)                      # the decode is the last thing a step does
-        in_flight.append(done)
-
-    if args.calibration_copy:
-        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(7)
-        b = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-        b.copy_(a)
-        torch.cuda.synchronize()
-        del a, b
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(timed=True)
-    torch.cuda.synchronize()
-    t_total = time.perf_counter() - t0
-    ms_per_step = t_total / args.steps * 1e3
-    value = 4 * L / (t_total / args.steps) / 1e9
-
-    # ---- results are what they should be (device-side comparison with the source tensors) ------
-    verified = all(torch.equal(a, b) for a, b in zip(fresh_own, shards[own])) and \
-        all(torch.equal(a, b) for a, b in zip(fresh_lost, shards[lost]))
-    if not verified:
-        log("[bench] ERROR: restored or reconstructed tensors differ from the originals")
-
-    enc_ms = sum(a.elapsed_time(b) for a, b in enc_events) / len(enc_events)
-    rec_ms = sum(a.elapsed_time(b) for a, b in rec_events) / len(rec_events)
-    enc_gbps = (k + 1) * L / (enc_ms * 1e-3) / 1e9
-    rec_gbps = (k + 1) * L / (rec_ms * 1e-3) / 1e9
-
-    # ---- each stage alone --------------------------------------------------------------------
-    def pct(x, peak):
-        return round(100.0 * x / peak, 1)
-
-    def measure_stages():
-        def timed_alone(fn, stream, reps=20, warm=3):
-            """Median of `reps` timed repetitions after `warm` untimed ones."""
-            for _ in range(warm):
-                fn()
-            torch.cuda.synchronize()
-            ts = []
-            for _ in range(reps):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                torch.cuda.synchronize()
-                e0.record(stream)
-                fn()
-                e1.record(stream)
-                e1.synchronize()
-                ts.append(e0.elapsed_time(e1) * 1e-3)
-            ts.sort()
-            return ts[len(ts) // 2]
-
-        packed = torch.empty(L, dtype=torch.uint8, device=dev)
-        t_pack = timed_alone(lambda: reft.reft_pack_device(plan, p_own, packed, s_xor), s_xor)
-        t_unpack = timed_alone(lambda: reft.reft_unpack_device(plan, packed, p_fresh_own, s_xor), s_xor)
-        t_enc = timed_alone(lambda: reft.reft_parity_encode(plan, p_all, k, parity, s_xor), s_xor)
-        t_rec = timed_alone(lambda: reft.reft_reconstruct_spans(plan, p_surv, k, lost, parity2,
-                                                                p_fresh_lost, s_xor), s_xor)
-        del packed
-        # the paper's rotated placement: all k members' units, then the decode of the lost member
-        Lseg = reft.reft_segment_bytes(plan, k)
-        units = [torch.empty(Lseg, dtype=torch.uint8, device=dev) for _ in range(k)]
-        p_units = reft.ptr_array(units)
-
-        def all_units():
-            for i in range(k):
-                reft.reft_parity_encode_rotated(plan, p_all, k, i, units[i], s_xor)
-        t_rot = timed_alone(all_units, s_xor)
-        t_rotdec = timed_alone(lambda: reft.reft_reconstruct_rotated(plan, p_all, p_units, k, lost,
-                                                                     p_fresh_lost, s_xor), s_xor)
-        rot_ok = all(torch.equal(a, b) for a, b in zip(fresh_lost, shards[lost]))
-        del units
-
-        def snap():
-            s_snap.wait_stream(s_xor)
-            reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_snap, s_copy)
-            s_xor.wait_stream(snap_done_stream)
-        def rest():
-            s_h2d.wait_stream(s_xor)
-            reft.reft_restore(plan, host_snap, stag_load, p_fresh_own, s_h2d, s_load)
-            s_xor.wait_stream(s_load)
-        t_snap = timed_alone(snap, s_xor, reps=5, warm=1)
-        t_rest = timed_alone(rest, s_xor, reps=5, warm=1)
-
-        stages = {
-            "pack_kernel_GBps": round(2 * L / t_pack / 1e9, 1),
-            "unpack_kernel_GBps": round(2 * L / t_unpack / 1e9, 1),
-            "parity_encode_GBps": round((k + 1) * L / t_enc / 1e9, 1),
-            "reconstruct_GBps": round((k + 1) * L / t_rec / 1e9, 1),
-            "rotated_units_GBps": round(k * k * Lseg / t_rot / 1e9, 1),
-            "rotated_decode_GBps": round(k * (k - 1) * Lseg / t_rotdec / 1e9, 1),
-            "rotated_decode_verified": bool(rot_ok),
-            "snapshot_d2h_GBps": round(L / t_snap / 1e9, 2),
-            "restore_h2d_GBps": round(L / t_rest / 1e9, 2),
-        }
-        stages["pct_hbm_peak"] = {n: pct(stages[n], HBM_PEAK_GBPS) for n in
-                                  ("pack_kernel_GBps", "unpack_kernel_GBps", "parity_encode_GBps",
-                                   "reconstruct_GBps", "rotated_units_GBps", "rotated_decode_GBps")}
-        stages["pct_link_peak"] = {n: pct(stages[n], LINK_PEAK_GBPS) for n in
-                                   ("snapshot_d2h_GBps", "restore_h2d_GBps")}
-
-        return stages
-
-    stages = None if args.no_stages else measure_stages()
-
-    # ---- concurrent training proxy: bf16 8192^3 GEMMs beside the save phase -------------------
-    gemm = None
-    if args.gemm_seconds >= 0:
-        n = 8192
-        A = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
-        B = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
-        C = torch.empty(n, n, device=dev, dtype=torch.bfloat16)
-        cur = torch.cuda.current_stream()
-
-        def gemms(count):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(cur)
-            for _ in range(count):
-                torch.matmul(A, B, out=C)
-            e1.record(cur)
-            return e0, e1
-
-        e0, e1 = gemms(20)
-        torch.cuda.synchronize()
-        e0, e1 = gemms(50)
-        torch.cuda.synchronize()
-        t_one = e0.elapsed_time(e1) * 1e-3 / 50
-        # the save phase alone
-        torch.cuda.synchronize()
-        ts0 = time.perf_counter()
-        save_phase(False)
-        torch.cuda.synchronize()
-        t_save = time.perf_counter() - ts0
-        ts0 = time.perf_counter()
-        save_phase(False)
-        torch.cuda.synchronize()
-        t_save = min(t_save, time.perf_counter() - ts0)
-        span = args.gemm_seconds if args.gemm_seconds > 0 else t_save
-        count = max(10, int(span / t_one))
-        e0, e1 = gemms(count)
-        torch.cuda.synchronize()
-        t_alone = e0.elapsed_time(e1) * 1e-3
-        if args.snapshot_wgs:
-            reft.reft_set_tunable("max_wgs", args.snapshot_wgs)
-        torch.cuda.synchronize()
-        ts0 = time.perf_counter()
-        save_phase(False)
-        e0, e1 = gemms(count)
-        e1.synchronize()
-        t_with = e0.elapsed_time(e1) * 1e-3
-        torch.cuda.synchronize()
-        t_save_with = time.perf_counter() - ts0
-        reft.reft_set_tunable("max_wgs", 0)
-        gemm = {
-            "gemm": "bf16 8192x8192x8192 (torch.matmul as the load)",
-            "gemms": count,
-            "tflops_alone": round(2 * n ** 3 * count / t_alone / 1e12, 1),
-            "t_alone_s": round(t_alone, 4),
-            "t_with_snapshot_s": round(t_with, 4),
-            "slowdown_pct": round(100.0 * (t_with - t_alone) / t_alone, 2),
-            "save_phase_alone_s": round(t_save, 4),
-            "save_phase_with_gemm_s": round(t_save_with, 4),
-            "snapshot_wgs": args.snapshot_wgs,
-        }
-        del A, B, C
-
-    # ---- bubble-aware scheduling of the save phase on a synthetic stage timeline ------------------
-    has = None
-    if save_staged and not args.no_has and args.gemm_seconds >= 0:
-        has = has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, host_snap,
-                       host_par, stag_save, stag_psave, s_snap, s_copy, s_xor, iterations=3)
-
-    # ---- the CPU oracle on a bounded sample of the same workload --------------------------------
-    cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(wl, shards, own, lost, args.cpu_sample_mib << 20)
-
+    value = main_rec["value_GBps"]
     record = {
         "metric": "snapshot+parity GB/s (% HBM/host-link peak); concurrent step slowdown %",
-        "value": round(value, 2),
+        "value": value,
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 2),
+        "ms_per_step": main_rec["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "u8",
         "data": "synthetic",
         "config": {
-            "workload": f"config {wl.cfg}: {wl.description}",
-            "k": k, "spans": T, "stream_bytes": L, "buckets": len(wl.bucket_nbytes),
-            "step": "XOR parity, snapshot own shard + parity to pinned host, then "
-                    "restore shard + parity from host and reconstruct the lost shard",
-            "encode_beside_copies": bool(args.overlap_encode),
-            "value_bytes_per_step": 4 * L,
+            "workload": main_rec["workload"],
+            "k": main_rec["k"], "spans": main_rec["spans"], "stream_bytes": main_rec["stream_bytes"],
+            "buckets": main_rec["buckets"],
+            "step": "XOR parity, snapshot own shard + parity to pinned host, restore shard + parity "
+                    "from host and reconstruct the lost shard; consecutive steps " +
+                    ("run one after the other" if args.serial else
+                     "are pipelined so that snapshots and restores share the link, full duplex; the "
+                     "XOR kernels run with the link idle"),
+            "schedule": "serial" if args.serial else "pipelined",
+            "value_bytes_per_step": 4 * main_rec["stream_bytes"],
             "save_path": args.save_path, "load_path": args.load_path,
-            "staging_mib": args.staging_mib,
-            "link_wgs": reft.reft_get_tunable("link_wgs"),
-            "pct_link_peak_one_direction": pct(value, LINK_PEAK_GBPS),
-            "note": "the own shard's restore overlaps the parity's snapshot: the link runs both "
-                    "directions at once, so the step can exceed one direction's peak",
+            "staged_snapshot": main_rec["staged_snapshot"],
+            "dma_streams": reft.reft_get_tunable("dma_streams"),
+            "pct_link_duplex_peak": main_rec["pct_link_duplex_peak"],
+            "link_peak_GBps": {"one_direction": LINK_PEAK_GBPS, "duplex": LINK_DUPLEX_PEAK_GBPS},
+            "note": "value counts bytes in both directions of the host link, so it is held against "
+                    "the duplex peak; each direction alone is under stages.pct_link_peak",
         },
-        "verified": bool(verified),
-        "roofline": {
-            "kernel": f"k_gather_burst<{k}> (parity encode over {k} span tables)"
-                      if reft.reft_get_tunable("burst") and k >= reft.reft_get_tunable("burst_min_rows")
-                      else f"k_gather<{k}> (parity encode over {k} span tables)",
-            "bound": "hbm",
-            "achieved": round(enc_gbps, 1),
-            "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s",
-            "frac": round(enc_gbps / HBM_PEAK_GBPS, 4),
-            "traffic": measured_traffic(wl.cfg) if k == 8 else None,
-            "bytes_per_launch": (k + 1) * L,
-            "avg_launch_ms": round(enc_ms, 3),
-            "reconstruct_achieved": round(rec_gbps, 1),
-            "reconstruct_avg_launch_ms": round(rec_ms, 3),
-        },
-        "stages": stages,
-        "gemm_proxy": gemm,
-        "stage_timeline": has,
-        "cpu_baseline": cpu,
+        "verified": bool(main_rec["verified"] and all(r["verified"] for r in per.values())),
+        "roofline": main_rec["roofline"],
+        "stages": main_rec.get("stages"),
+        "gemm_proxy": main_rec.get("gemm_proxy"),
+        "stage_timeline": main_rec.get("stage_timeline"),
+        "cpu_baseline": main_rec.get("cpu_baseline"),
+        "per_config": per,
     }
-    reft.reft_plan_destroy(plan)
-    reft.reft_plan_destroy(pplan)
     print(json.dumps(record), flush=True)
-    return 0 if verified else 1
+    return 0 if record["verified"] else 1
 
 
-def has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, host_snap, host_par,
-             stag_save, stag_psave, s_snap, s_copy, s_xor, iterations=5):
+def has_demo(b, iterations=5):
     """Hierarchical scheduling of one snapshot per iteration on a synthetic pipeline-stage timeline
     (Algorithm 1): each iteration is an idle bubble followed by a burst of bf16 GEMMs.
 
@@ -508,20 +702,22 @@ def has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, 
 
     t_ss = size / B_io (EstimateSnapshotTime) with B_io measured here; the bubble length is an
     input (the printed EstimateBubbleTime formula is not used)."""
-    dev = torch.device("cuda:0")
+    torch, reft, args = b.torch, b.reft, b.args
+    plan, pplan, L, k = b.plan, b.pplan, b.L, b.k
+    s_snap, s_copy, s_xor = b.s_pack, b.s_save, b.s_load
     n = 8192
-    A = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
-    B = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
-    C = torch.empty(n, n, device=dev, dtype=torch.bfloat16)
+    A = torch.randn(n, n, device=b.dev, dtype=torch.bfloat16)
+    B = torch.randn(n, n, device=b.dev, dtype=torch.bfloat16)
+    C = torch.empty(n, n, device=b.dev, dtype=torch.bfloat16)
     s_gemm = torch.cuda.current_stream()
     nb = reft.reft_plan_num_buckets(plan)
     t_bubble = args.bubble_ms * 1e-3
 
     # B_io: the direct transport's rate on this box
-    reft.reft_snapshot_pack(plan, p_own, None, host_snap, s_snap, None)
+    reft.reft_snapshot_pack(plan, b.p_own, None, b.host_snap, s_snap, None)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    reft.reft_snapshot_pack(plan, p_own, None, host_snap, s_snap, None)
+    reft.reft_snapshot_pack(plan, b.p_own, None, b.host_snap, s_snap, None)
     torch.cuda.synchronize()
     b_io = L / (time.perf_counter() - t0)
     t_ss = L / b_io
@@ -537,25 +733,25 @@ def has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, 
         return ev
 
     def save_all_beside_compute():
-        reft.reft_parity_encode(plan, p_all, k, parity, s_xor)
-        reft.reft_snapshot_pack(plan, p_own, stag_save, host_snap, s_snap, s_copy)
+        reft.reft_parity_encode(plan, b.p_all, k, b.parity, s_xor)
+        reft.reft_snapshot_pack(plan, b.p_own, b.stag_save, b.host_snap, s_snap, s_copy)
         s_snap.wait_stream(s_xor)
-        reft.reft_snapshot_pack(pplan, p_par, stag_psave, host_par, s_snap, s_copy)
+        reft.reft_snapshot_pack(pplan, b.p_par, b.stag_psave, b.host_par, s_snap, s_copy)
 
     def iteration(policy):
         t_start = time.perf_counter()
         if policy == "has":                      # layer 1: the bubble
-            reft.reft_parity_encode(plan, p_all, k, parity, s_xor)
-            reft.reft_snapshot_pack_range(plan, p_own, None, host_snap, 0, b_cut, s_snap, None)
+            reft.reft_parity_encode(plan, b.p_all, k, b.parity, s_xor)
+            reft.reft_snapshot_pack_range(plan, b.p_own, None, b.host_snap, 0, b_cut, s_snap, None)
         while time.perf_counter() - t_start < t_bubble:
             time.sleep(0.0005)
         done = burst()
         if policy == "naive":
             save_all_beside_compute()
         elif policy == "has":                    # layer 2: beside compute, copies only
-            reft.reft_snapshot_pack_range(plan, p_own, stag_save, host_snap, b_cut, nb, s_snap, s_copy)
+            reft.reft_snapshot_pack_range(plan, b.p_own, b.stag_save, b.host_snap, b_cut, nb, s_snap, s_copy)
             s_snap.wait_stream(s_xor)
-            reft.reft_snapshot_pack(pplan, p_par, stag_psave, host_par, s_snap, s_copy)
+            reft.reft_snapshot_pack(pplan, b.p_par, b.stag_psave, b.host_par, s_snap, s_copy)
         done.synchronize()
         t_compute_done = time.perf_counter()
         torch.cuda.synchronize()                 # the snapshot must have landed before the next one
@@ -572,7 +768,7 @@ def has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, 
     base = res["none"][0]
     return {
         "metric": "iteration time of a synthetic pipeline stage with one snapshot per iteration",
-        "workload": f"config {args.config}",
+        "workload": f"config {b.wl.cfg}",
         "bubble_ms": args.bubble_ms, "burst_gemms": args.burst_gemms,
         "B_io_GBps": round(b_io / 1e9, 2), "t_ss_ms": round(t_ss * 1e3, 1),
         "cut_bytes": cut, "cut_bucket": b_cut, "buckets": nb,
@@ -583,21 +779,22 @@ def has_demo(args, torch, reft, plan, pplan, L, k, p_own, p_all, p_par, parity, 
 
 
 def measured_traffic(cfg: int):
-    """HBM bytes per launch of the encode kernel from the committed rocprofv3 counter runs
-    (FETCH_SIZE and WRITE_SIZE, each scaled by a copy of known size), or None if no such profile
-    exists for this configuration."""
-    path = os.path.join(ROOT, "profiles", f"config{cfg}_k_gather_burst8_hbm_traffic.txt")
+    """(HBM bytes per launch of the encode kernel, the tracked file they come from): FETCH_SIZE and
+    WRITE_SIZE of a committed rocprofv3 counter run, each scaled by a copy of known size.  A
+    calibrated figure from an earlier run of the same command, not measured by this run.
+    (None, None) if no such profile exists for this configuration."""
+    name = f"config{cfg}_k_gather_burst8_hbm_traffic.txt"
     try:
         kv = {}
-        for line in open(path):
+        for line in open(os.path.join(ROOT, "profiles", name)):
             if "=" in line and line.split("=")[0].strip().startswith("traffic_"):
                 key, _, val = line.partition("=")
                 kv[key.strip()] = val.strip()
         if int(kv.get("traffic_config", -1)) == cfg:
-            return int(kv["traffic_bytes"])
+            return int(kv["traffic_bytes"]), f"profiles/{name} (rocprofv3 --pmc run of this command)"
     except (OSError, ValueError, KeyError):
         pass
-    return None
+    return None, None
 
 
 def cpu_baseline(wl, shards, own, lost, sample_bytes):
