@@ -783,7 +783,7 @@ def measured_traffic(cfg: int):
     WRITE_SIZE of a committed rocprofv3 counter run, each scaled by a copy of known size.  A
     calibrated figure from an earlier run of the same command, not measured by this run.
     (None, None) if no such profile exists for this configuration."""
-    name = f"config{cfg}_k_gather_burst8_hbm_traffic.txt"
+    name = f"config{cfg}_kernels_hbm_traffic.txt"
     try:
         kv = {}
         for line in open(os.path.join(ROOT, "profiles", name)):
