@@ -305,6 +305,42 @@ int reft_reconstruct_rotated(reft_plan *plan, const void *const *shard_span_ptrs
                              const void *const *parity_ptrs, uint32_t k, uint32_t lost,
                              void *const *out_span_ptrs, reft_stream stream);
 
+/* ---- several redundancy strategies at once (section 4.2, Collaborative Redundant Protection) -------
+ * The paper lets several strategies protect a group together - redundant copies (ARC: member i
+ * also snapshots the shard of member (i + d) mod k; one strategy per offset d) and the rotated
+ * parity units (AEC) - and states that N strategies survive N lost members.  What survives a given
+ * loss depends on where the redundancy lay, so the library plans the recovery from the set of lost
+ * members (host integer logic, no GPU needed); the steps themselves are the ordinary calls:
+ *   REFT_RECOVER_COPY    reft_restore of the duplicate of `member`'s shard that surviving member
+ *                        `source` keeps under copy_offsets[which];
+ *   REFT_RECOVER_DECODE  reft_reconstruct_rotated of `member` from all other members' shards and
+ *                        parity units.  Possible only when `member` is the only one lost: a second
+ *                        lost member takes along the unit that covers one of its segments.
+ * A lost member with a surviving duplicate is copied (the cheaper step); two redundant copies with
+ * different offsets survive any two losses for k >= 3, while a copy plus the parity units survive
+ * two losses only if neither lost member kept the other's duplicate.
+ *
+ * k             members of the group, 2 <= k <= REFT_MAX_K.
+ * copy_offsets  n_copies offsets d, 1 <= d < k (may be NULL with n_copies == 0).
+ * parity_units  non-zero if every member also keeps its rotated parity unit.
+ * lost[k]       1 = member lost.
+ * steps         receives one step per recoverable lost member, in member order (room for k).
+ * nsteps        receives their number.
+ * Returns REFT_OK if every lost member is recoverable, REFT_EUNRECOVERABLE if some are not (the
+ * steps of those that are still come back), REFT_EINVAL for bad arguments.
+ */
+#define REFT_RECOVER_COPY   1
+#define REFT_RECOVER_DECODE 2
+typedef struct reft_recovery_step {
+    uint32_t member;   /* the lost member this step recovers                                     */
+    uint32_t how;      /* REFT_RECOVER_COPY or REFT_RECOVER_DECODE                                */
+    uint32_t source;   /* COPY: the surviving member that keeps the duplicate                    */
+    uint32_t which;    /* COPY: index into copy_offsets of the strategy the duplicate belongs to */
+} reft_recovery_step;
+int reft_recovery_plan(uint32_t k, const uint32_t *copy_offsets, uint32_t n_copies,
+                       int parity_units, const uint8_t *lost, reft_recovery_step *steps,
+                       uint32_t *nsteps);
+
 /* ---- S5 + S7: load a shard from pinned host memory back into its tensors (section 4.3, step 1) ---
  * The inverse of reft_snapshot_pack, with the same two transports: staged (staging != NULL:
  * large pieces by hipMemcpyAsync on copy_stream straight into their tensors, runs of small pieces

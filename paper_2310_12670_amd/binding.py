@@ -22,7 +22,8 @@ __all__ = [
     "reft_snapshot_pack", "reft_snapshot_pack_range", "reft_plan_bucket_of", "reft_snapshot_wait",
     "reft_snapshot_query", "reft_ckpt_create", "reft_ckpt_destroy", "reft_ckpt_begin",
     "reft_ckpt_commit", "reft_ckpt_latest", "reft_ckpt_wait", "REFT_EBUSY",
-    "reft_plan_staged_work", "reft_plan_burst_stats",
+    "reft_plan_staged_work", "reft_plan_burst_stats", "reft_recovery_plan",
+    "REFT_RECOVER_COPY", "REFT_RECOVER_DECODE",
     "reft_pack_device", "reft_unpack_device", "reft_parity_encode", "reft_parity_encode_noalloc",
     "reft_reconstruct",
     "reft_reconstruct_spans", "reft_segment_bytes", "reft_parity_encode_rotated",
@@ -32,6 +33,7 @@ __all__ = [
 
 REFT_OK, REFT_EINVAL, REFT_ESIZE, REFT_EHIP, REFT_EUNRECOVERABLE, REFT_EBUSY = 0, -1, -2, -3, -4, -5
 REFT_MAX_K = 32
+REFT_RECOVER_COPY, REFT_RECOVER_DECODE = 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libreft.so")
@@ -90,6 +92,7 @@ def _load():
         "reft_plan_staged_work": (i, [vp, pu64, pu64]),
         "reft_plan_burst_stats": (i, [vp, pu64]),
         "reft_ckpt_wait": (i, [vp]),
+        "reft_recovery_plan": (i, [u32, vp, u32, i, vp, vp, ctypes.POINTER(u32)]),
         "reft_reconstruct": (i, [vp, u32, vp, u64, vp, ctypes.POINTER(u32), vp]),
         "reft_reconstruct_spans": (i, [vp, vp, u32, u32, vp, vp, vp]),
         "reft_segment_bytes": (u64, [vp, u32]),
@@ -299,6 +302,23 @@ def reft_plan_burst_stats(plan):
     v = (ctypes.c_uint64 * 4)()
     _check(_load().reft_plan_burst_stats(plan, v))
     return tuple(int(x) for x in v)
+
+
+def reft_recovery_plan(k: int, copy_offsets: Sequence[int], parity_units: bool, lost: Sequence[int]):
+    """``lost``: the lost members' indices.  Returns (steps, recoverable) with steps a list of
+    (member, how, source, which); ``recoverable`` is False where the library answers
+    REFT_EUNRECOVERABLE (the steps of the members that can be recovered still come back)."""
+    lib = _load()
+    flags = (ctypes.c_uint8 * max(1, k))(*[1 if x in set(lost) else 0 for x in range(k)])
+    offs = (ctypes.c_uint32 * max(1, len(copy_offsets)))(*[int(d) for d in copy_offsets])
+    steps = (ctypes.c_uint32 * (4 * max(1, k)))()
+    n = ctypes.c_uint32()
+    rc = lib.reft_recovery_plan(int(k), offs, len(copy_offsets), 1 if parity_units else 0, flags,
+                                steps, ctypes.byref(n))
+    if rc not in (REFT_OK, REFT_EUNRECOVERABLE):
+        _check(rc)
+    out = [tuple(steps[4 * j:4 * j + 4]) for j in range(n.value)]
+    return out, rc == REFT_OK
 
 
 def reft_snapshot_wait(plan) -> None:

@@ -1721,6 +1721,49 @@ extern "C" int reft_reconstruct_rotated(reft_plan *p, const void *const *shard_s
 }
 
 // ------------------------------------------------------------------------------------------------
+// several redundancy strategies at once (section 4.2): which lost members can be recovered, how
+// ------------------------------------------------------------------------------------------------
+extern "C" int reft_recovery_plan(uint32_t k, const uint32_t *copy_offsets, uint32_t n_copies,
+                                  int parity_units, const uint8_t *lost, reft_recovery_step *steps,
+                                  uint32_t *nsteps)
+{
+    if (!lost || !steps || !nsteps) return fail(REFT_EINVAL, "reft_recovery_plan: null argument");
+    *nsteps = 0;
+    if (k < 2 || k > REFT_MAX_K)
+        return fail(REFT_EINVAL, "reft_recovery_plan: k = %u outside [2, %d]", k, REFT_MAX_K);
+    if (n_copies && !copy_offsets) return fail(REFT_EINVAL, "reft_recovery_plan: null offsets");
+    for (uint32_t a = 0; a < n_copies; ++a)
+        if (copy_offsets[a] < 1 || copy_offsets[a] >= k)
+            return fail(REFT_EINVAL, "reft_recovery_plan: copy offset %u outside [1, %u)",
+                        copy_offsets[a], k);
+    uint32_t nlost = 0, stuck = 0, first_stuck = 0;
+    for (uint32_t x = 0; x < k; ++x) nlost += lost[x] ? 1u : 0u;
+    for (uint32_t x = 0; x < k; ++x) {
+        if (!lost[x]) continue;
+        bool done = false;
+        for (uint32_t a = 0; a < n_copies && !done; ++a) {
+            const uint32_t holder = (x + k - copy_offsets[a]) % k;      // holder + d = x (mod k)
+            if (lost[holder]) continue;
+            steps[(*nsteps)++] = reft_recovery_step{x, REFT_RECOVER_COPY, holder, a};
+            done = true;
+        }
+        // every segment of x is covered by the unit of another member: all of them must be there
+        if (!done && parity_units && nlost == 1) {
+            steps[(*nsteps)++] = reft_recovery_step{x, REFT_RECOVER_DECODE, 0, 0};
+            done = true;
+        }
+        if (!done && stuck++ == 0) first_stuck = x;
+    }
+    if (stuck)
+        return fail(REFT_EUNRECOVERABLE,
+                    "reft_recovery_plan: %u of the %u lost members cannot be recovered (first: "
+                    "member %u): no surviving duplicate%s", stuck, nlost, first_stuck,
+                    parity_units ? ", and with more than one member lost a parity unit is missing too"
+                                 : "");
+    return REFT_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
 // S6: single-loss decode
 // ------------------------------------------------------------------------------------------------
 extern "C" int reft_reconstruct(const void *const *shards, uint32_t k, const void *parity,
