@@ -572,7 +572,7 @@ def run_config(args, cfg, torch, reft, pinned, streams, primary):
             },
         }
         if not args.no_stages:
-            out["stages"] = measure_stages(b, args.stage_reps if primary else min(args.stage_reps, 7))
+            out["stages"] = measure_stages(b, args.stage_reps)
         if args.gemm_seconds >= 0:
             out["gemm_proxy"] = gemm_proxy(b)
         if primary and b.save_staged and not args.no_has and args.gemm_seconds >= 0:

@@ -131,10 +131,14 @@ int reft_plan_staged_work(reft_plan *plan, uint64_t *gather_launches, uint64_t *
  *       bubbles, recovery): kernels that keep the link's write path full slow down kernels
  *       running beside them.  host_dst must be device-accessible pinned memory (hipHostMalloc),
  *       else REFT_EINVAL.
- * Streams: the HIP runtime maps streams onto a few hardware queues (4 per process by default) in
- * the order in which they first get work, and two streams on one queue run in turn.  A snapshot
- * and a restore only overlap on the link (full duplex) if their copy streams sit on different
- * queues: give each its own stream and let both do some work early, in a fixed order.
+ * Streams: the HIP runtime deals streams onto a few hardware queues (4 per process by default) as
+ * they are created, whether they ever get work or not, and two streams on one queue run in turn.
+ * A snapshot and a restore only overlap on the link (full duplex) if their copy streams sit on
+ * different queues: give each its own stream, created early, and keep the process's stream count
+ * low (when reft_plan_staged_work reports no gather launches, one stream serves as pack_stream
+ * and copy_stream).  Queue depth: with several snapshots' copies queued ahead (thousands of
+ * hipMemcpyAsync calls) the runtime's device-to-host copies run at a fraction of their rate; wait
+ * for the previous snapshot (reft_snapshot_wait, an event) before queuing the next.
  * After the last bucket a completion event is recorded (see reft_snapshot_wait): the snapshot is
  * complete only when every bucket has landed (section 4.4: COMPLETED when all tensors are
  * snapshotted).  Postcondition: host_dst[0..L) == stream; host_dst[L..) untouched.
@@ -368,9 +372,11 @@ int reft_restore_wait(reft_plan *plan);
  *   "dma_streams"  staged transport: 1 (default) = all piece copies on copy_stream; 2 = they
  *                  alternate between copy_stream and a helper stream owned by the plan (forked from
  *                  and joined to copy_stream, default priority), which hides the set-up gap between
- *                  consecutive copies (53.8 -> 56.7 GB/s) - but only while the process has a free
- *                  hardware queue for it: with more active streams than hardware queues (4 by
- *                  default) the helper shares a queue and the snapshot gets slower instead.
+ *                  consecutive copies (56.2 -> 56.9 GB/s) - but only while the process has a free
+ *                  hardware queue for it: with more streams than hardware queues (4 by default)
+ *                  the helper shares a queue and transfers get slower instead.  The helper stream
+ *                  is created with the plan if the tunable is 2 at that time, else by the first
+ *                  call that wants it.
  *   "graph_copies" staged transport: 0 (default) = the piece copies are hipMemcpyAsync calls; 1 = they
  *                  are the independent memcpy nodes of a hipGraph that the plan builds once per
  *                  (tensors, host buffer, bucket range) and replays, 2 = the same as a chain of
