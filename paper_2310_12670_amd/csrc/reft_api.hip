@@ -244,8 +244,6 @@ struct reft_plan {
     hipStream_t last_pack_stream = nullptr;
     // device address of the library's static scratch on this plan's GPU (see reft_parity_encode_noalloc)
     unsigned char *scratch = nullptr;
-    // ring of burst counter blocks in static device memory, shared by all plans of the GPU
-    uint32_t *static_ctr = nullptr;
     // bucket pipelines
     Event pack_filled[kGroups], pack_free[kGroups], pack_done, pack_begin, rest_begin;
     Event rest_filled[kGroups], rest_free[kGroups], rest_done, rest_copied;
@@ -616,7 +614,6 @@ extern "C" int reft_plan_create(const uint64_t *span_nbytes, uint64_t T,
     const DeviceStatics *ds = nullptr;
     if ((rc = device_statics(&ds))) return rc;
     p->scratch = ds->scratch;
-    p->static_ctr = ds->ctr;
     for (int i = 0; i < kRing; ++i) {
         if ((rc = make_event(p->ring[i].uploaded))) return rc;
         for (int u = 0; u < kUsers; ++u)

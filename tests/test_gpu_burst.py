@@ -293,3 +293,36 @@ def test_concurrent_launches_on_several_streams(dev):
     for o in outs:
         for t in o:
             assert np.array_equal(t.cpu().numpy(), want)
+
+
+def test_burst_statistics_add_up(dev):
+    """reft_plan_burst_stats: every writer-wave round of the last burst launch is counted once, as
+    met, timed out or not waited; with waiting switched off nothing is counted."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(77)
+    sizes = [13 << 20, 12345, 1 << 20, 27 << 20]
+    L, k = sum(sizes), 6
+    shards = [[torch.randint(0, 256, (n,), dtype=torch.uint8, device=dev, generator=gen) for n in sizes]
+              for _ in range(k)]
+    want = oracle.encode([oracle.pack([oracle.as_bytes(t.cpu()) for t in sh]) for sh in shards])
+    plan = reft.reft_plan_create(sizes)
+    try:
+        assert reft.reft_plan_burst_stats(plan) == (0, 0, 0, 0)          # nothing launched yet
+        out = torch.empty(L, dtype=torch.uint8, device=dev)
+        stage = reft.reft_get_tunable("burst_stage_bytes")
+        nstages = -(-L // stage)
+        for polls in (6, 1, 0):
+            reft.reft_set_tunable("burst_max_polls", polls)
+            out.zero_()
+            reft.reft_parity_encode(plan, [t for sh in shards for t in sh], k, out)
+            met, late, skipped, groups = reft.reft_plan_burst_stats(plan)
+            assert np.array_equal(out.cpu().numpy(), want), polls
+            if polls == 0:
+                assert (met, late, skipped, groups) == (0, 0, 0, 0)
+            else:
+                # one writer-wave round per workgroup and round of the persistent grid (workgroup b
+                # takes stages b, b + grid, ...): at least one per stage, less than a grid more
+                assert nstages <= met + late + skipped < nstages + 2048, (polls, met, late, skipped)
+                assert groups >= 1
+    finally:
+        reft.reft_plan_destroy(plan)
