@@ -824,27 +824,33 @@ def cpu_baseline(wl, shards, own, lost, sample_bytes):
     def one_pass():
         t0 = time.perf_counter()
         streams = [oracle.pack_bucketed(cpu[own], buckets)]
+        t_pack = time.perf_counter()
         others = [oracle.pack(cpu[s]) for s in range(k) if s != own]   # peers' packed shards
-        t_peers = time.perf_counter()
         all_streams = others[:own] + streams + others[own:]
-        par = oracle.encode(all_streams)
-        back = oracle.unpack(streams[0], sizes)
-        rec = oracle.reconstruct([all_streams[s] for s in range(k) if s != lost], par)
-        back_lost = oracle.unpack(rec, sizes)
         t1 = time.perf_counter()
+        par = oracle.encode(all_streams)
+        t_enc = time.perf_counter()
+        back = oracle.unpack(streams[0], sizes)
+        t_unp = time.perf_counter()
+        rec = oracle.reconstruct([all_streams[s] for s in range(k) if s != lost], par)
+        t_rec = time.perf_counter()
+        back_lost = oracle.unpack(rec, sizes)
+        t_end = time.perf_counter()
         ok = all(np.array_equal(a, b) for a, b in zip(back_lost, cpu[lost])) and \
             all(np.array_equal(a, b) for a, b in zip(back, cpu[own]))
-        return t1 - t0, ok
+        # per operation, with the byte accounting of the GPU stages (HBM-side bytes)
+        ops = {"pack_GBps": 2 * Ls / (t_pack - t0), "encode_GBps": (k + 1) * Ls / (t_enc - t1),
+               "unpack_GBps": 2 * Ls / (t_unp - t_enc), "reconstruct_GBps": (k + 1) * Ls / (t_rec - t_unp)}
+        return t_end - t0, ok, {n: round(v / 1e9, 2) for n, v in ops.items()}
 
     out = {}
     threads_all = oracle.max_threads()
     for threads in (1, threads_all):
         oracle.set_threads(threads)
-        t, ok = one_pass()
-        out[threads] = (t, ok)
+        out[threads] = one_pass()
     oracle.set_threads(1)
-    t_all, ok_all = out[threads_all]
-    t_one, ok_one = out[1]
+    t_all, ok_all, ops_all = out[threads_all]
+    t_one, ok_one, ops_one = out[1]
     return {
         "value": round(4 * Ls / t_all / 1e9, 3),
         "unit": "GB/s",
@@ -852,8 +858,10 @@ def cpu_baseline(wl, shards, own, lost, sample_bytes):
         "kind": "oracle",
         "sample": f"first {nsp} spans of each of the {k} shards ({Ls} bytes per shard); one pass = "
                   f"pack own + pack peers + encode + unpack + reconstruct + unpack, {t_all:.2f} s",
+        "per_operation": ops_all,
         "single_thread_value": round(4 * Ls / t_one / 1e9, 3),
         "single_thread_seconds": round(t_one, 2),
+        "single_thread_per_operation": ops_one,
         "verified": bool(ok_all and ok_one),
     }
 
