@@ -69,7 +69,7 @@ def parse_args():
     ap.add_argument("--per-config", type=str, default="1,2,4",
                     help="configurations that get a shorter run of their own under per_config "
                          "(comma separated; '' = none)")
-    ap.add_argument("--per-config-steps", type=int, default=6)
+    ap.add_argument("--per-config-steps", type=int, default=8)
     ap.add_argument("--serial", action="store_true",
                     help="no pipelining across steps: a step's save starts when the previous "
                          "step's load has ended")
@@ -190,7 +190,7 @@ class Bench:
         # serves as pack_stream and copy_stream (a hardware queue less).
         self.s_pack = torch.cuda.Stream() if (self.save_staged and self.gathers) else self.s_save
         self.enc_events, self.dec_events = [], []
-        self.phases, self.tracing = [], False
+        self.phases, self.tracing, self.step_marks = [], False, []
         self.reset_pipeline()
 
     # ---- the step ---------------------------------------------------------------------------------
@@ -262,6 +262,10 @@ class Bench:
         self._phase("snapshot_parity", n, self.s_save, lambda: self.reft.reft_snapshot_pack(
             self.pplan, self.p_par, self.stag_psave, self.host_par, self.s_pack, self.s_save))
         self._mark("par_saved", n, self.s_save)
+        if self.tracing:                                          # one timing mark per timed step
+            e = self.torch.cuda.Event(enable_timing=True)
+            e.record(self.s_save)
+            self.step_marks.append(e)
 
     def _restore_shard(self, n):
         self._wait(self.s_load, "shard_saved", n)
@@ -345,6 +349,7 @@ def run_steps(b, steps, warmup):
     torch.cuda.synchronize()
     b.enc_events.clear()
     b.dec_events.clear()
+    b.step_marks.clear()
     b.tracing = True
     base = torch.cuda.Event(enable_timing=True)
     base.record(b.s_save)
@@ -368,7 +373,11 @@ def run_steps(b, steps, warmup):
     enc_ms = sum(x.elapsed_time(y) for x, y in b.enc_events) / len(b.enc_events)
     dec_ms = sum(x.elapsed_time(y) for x, y in b.dec_events) / len(b.dec_events)
     assert len(b.enc_events) == steps and len(b.dec_events) == steps
-    return t_total / steps, enc_ms, dec_ms, ok
+    # steady state: the median interval between the ends of consecutive steps' parity snapshots,
+    # the first three steps (pipeline fill, start-up transient) left out
+    gaps = sorted(x.elapsed_time(y) for x, y in zip(b.step_marks[3:], b.step_marks[4:]))
+    steady = gaps[len(gaps) // 2] * 1e-3 if gaps else None
+    return t_total / steps, enc_ms, dec_ms, ok, steady
 
 
 def measure_stages(b, reps):
@@ -539,7 +548,7 @@ def run_config(args, cfg, torch, reft, pinned, streams, primary):
             del x, y
         steps = args.steps if primary else args.per_config_steps
         warmup = args.warmup if primary else 1
-        t_step, enc_ms, dec_ms, ok = run_steps(b, steps, warmup)
+        t_step, enc_ms, dec_ms, ok, steady = run_steps(b, steps, warmup)
         value = 4 * L / t_step / 1e9
         enc_gbps = (k + 1) * L / (enc_ms * 1e-3) / 1e9
         dec_gbps = (k + 1) * L / (dec_ms * 1e-3) / 1e9
@@ -553,6 +562,13 @@ def run_config(args, cfg, torch, reft, pinned, streams, primary):
             "ms_per_step": round(t_step * 1e3, 2),
             "value_GBps": round(value, 2),
             "pct_link_duplex_peak": pct(value, LINK_DUPLEX_PEAK_GBPS),
+            "steady_state": None if steady is None else {
+                "ms_per_step": round(steady * 1e3, 2),
+                "GBps": round(4 * L / steady / 1e9, 2),
+                "pct_link_duplex_peak": pct(4 * L / steady / 1e9, LINK_DUPLEX_PEAK_GBPS),
+                "note": "median interval between consecutive steps inside the timed region (HIP "
+                        "events), fill, drain and the first three steps left out; context for "
+                        "value, which is the whole timed region"},
             "verified": bool(ok),
             "roofline": {
                 "kernel": (f"k_gather_burst<{k}>" if burst_on else f"k_gather<{k}>") +
@@ -672,6 +688,7 @@ def main() -> int:
             "staged_snapshot": main_rec["staged_snapshot"],
             "dma_streams": reft.reft_get_tunable("dma_streams"),
             "pct_link_duplex_peak": main_rec["pct_link_duplex_peak"],
+            "steady_state": main_rec["steady_state"],
             "link_peak_GBps": {"one_direction": LINK_PEAK_GBPS, "duplex": LINK_DUPLEX_PEAK_GBPS},
             "note": "value counts bytes in both directions of the host link, so it is held against "
                     "the duplex peak; each direction alone is under stages.pct_link_peak",
