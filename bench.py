@@ -415,6 +415,10 @@ def measure_stages(b, reps):
                      reft.reft_plan_burst_stats(plan)))
     t_rec = timed_alone(lambda: reft.reft_reconstruct_spans(plan, b.p_surv, k, b.lost, b.parity2,
                                                             b.p_fresh_lost, s), s)
+    # pack + encode in one pass (the own shard is read once for both)
+    t_fused = timed_alone(lambda: reft.reft_parity_encode_pack(plan, b.p_all, k, b.own, b.parity,
+                                                               packed, s), s)
+    fused_ok = bool(torch.equal(packed, torch.cat([t.reshape(-1).view(torch.uint8) for t in b.shards[b.own]])))
     del packed
     # the paper's rotated placement: all k members' units, then the decode of the lost member
     Lseg = reft.reft_segment_bytes(plan, k)
@@ -454,6 +458,10 @@ def measure_stages(b, reps):
         "runtime_copy_GBps": round(2 * L / t_blit / 1e9, 1),
         "parity_encode_GBps": round((k + 1) * L / t_enc / 1e9, 1),
         "reconstruct_GBps": round((k + 1) * L / t_rec / 1e9, 1),
+        "fused_pack_encode_GBps": round((k + 2) * L / t_fused / 1e9, 1),
+        "fused_pack_encode": {"ms": round(t_fused * 1e3, 3), "encode_then_pack_ms": round((t_enc + t_pack) * 1e3, 3),
+                              "hbm_bytes": (k + 2) * L, "encode_then_pack_hbm_bytes": (k + 3) * L,
+                              "packed_copy_verified": fused_ok},
         "rotated_units_GBps": round(k * k * Lseg / t_rot / 1e9, 1),
         "rotated_decode_GBps": round(k * (k - 1) * Lseg / t_rotdec / 1e9, 1),
         "rotated_decode_verified": bool(rot_ok),
@@ -467,8 +475,8 @@ def measure_stages(b, reps):
     }
     stages["pct_hbm_peak"] = {n: pct(stages[n], HBM_PEAK_GBPS) for n in
                               ("pack_kernel_GBps", "unpack_kernel_GBps", "copy_ceiling_GBps",
-                               "parity_encode_GBps", "reconstruct_GBps", "rotated_units_GBps",
-                               "rotated_decode_GBps")}
+                               "parity_encode_GBps", "reconstruct_GBps", "fused_pack_encode_GBps",
+                               "rotated_units_GBps", "rotated_decode_GBps")}
     stages["pct_link_peak"] = {"snapshot_d2h_GBps": pct(stages["snapshot_d2h_GBps"], LINK_PEAK_GBPS),
                                "restore_h2d_GBps": pct(stages["restore_h2d_GBps"], LINK_PEAK_GBPS),
                                "duplex_GBps": pct(stages["duplex_GBps"], LINK_DUPLEX_PEAK_GBPS)}

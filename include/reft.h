@@ -226,6 +226,24 @@ int reft_unpack_device(reft_plan *plan, const void *src_dev, uint64_t src_bytes,
 int reft_parity_encode(reft_plan *plan, const void *const *shard_span_ptrs, uint32_t k,
                        void *parity_dev, reft_stream stream);
 
+/* ---- S1 + S4 in one pass: parity of the k shards and the packed stream of one of them ------------
+ * parity_dev as for reft_parity_encode; packed_dev[0..L) = the stream of shard `own` (what
+ * reft_pack_device gives).  One kernel reads the k shards once and writes both: (k + 2) L bytes of
+ * HBM traffic instead of the (k + 3) L of an encode followed by a pack ("convert local snapshot
+ * segments into parity data" while they are being gathered, section 3).  For a scheduler that
+ * gathers and encodes in a bubble and lets two large copies (packed shard, parity) leave beside
+ * computation, or where many small tensors would be gathered by a kernel anyway.
+ * The single pass is taken where the write-burst kernel applies (see "burst"), with at most 8
+ * shards, parity_dev and packed_dev aligned alike modulo 16, "unroll" 4 and "nontemporal" 1, and
+ * "burst_stage_bytes" <= 36864 (two LDS images per half); otherwise the call runs the encode and
+ * the pack as two launches, with the same result.
+ * own < k; packed_cap >= L (REFT_ESIZE); neither buffer may overlap a span or the other.
+ * Errors: REFT_EINVAL, REFT_ESIZE, REFT_EHIP.
+ */
+int reft_parity_encode_pack(reft_plan *plan, const void *const *shard_span_ptrs, uint32_t k,
+                            uint32_t own, void *parity_dev, void *packed_dev, uint64_t packed_cap,
+                            reft_stream stream);
+
 /* ---- reft_parity_encode for callers that cannot allocate ------------------------------------------
  * For code that may not call hipMalloc while it runs: work under HIP graph capture, tight serving
  * loops, harnesses that forbid allocation.  Same arguments, same result as reft_parity_encode; the

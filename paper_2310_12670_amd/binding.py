@@ -25,7 +25,7 @@ __all__ = [
     "reft_plan_staged_work", "reft_plan_burst_stats", "reft_recovery_plan",
     "REFT_RECOVER_COPY", "REFT_RECOVER_DECODE",
     "reft_pack_device", "reft_unpack_device", "reft_parity_encode", "reft_parity_encode_noalloc",
-    "reft_reconstruct",
+    "reft_parity_encode_pack", "reft_reconstruct",
     "reft_reconstruct_spans", "reft_segment_bytes", "reft_parity_encode_rotated",
     "reft_reconstruct_rotated", "reft_restore", "reft_restore_wait",
     "reft_set_tunable", "reft_get_tunable", "reft_last_error", "reft_version",
@@ -89,6 +89,7 @@ def _load():
         "reft_unpack_device": (i, [vp, vp, u64, vp, vp]),
         "reft_parity_encode": (i, [vp, vp, u32, vp, vp]),
         "reft_parity_encode_noalloc": (i, [vp, vp, u32, vp, vp]),
+        "reft_parity_encode_pack": (i, [vp, vp, u32, u32, vp, vp, u64, vp]),
         "reft_plan_staged_work": (i, [vp, pu64, pu64]),
         "reft_plan_burst_stats": (i, [vp, pu64]),
         "reft_ckpt_wait": (i, [vp]),
@@ -346,6 +347,14 @@ def reft_parity_encode(plan, shard_span_ptrs, k: int, parity_dev, stream=None) -
     """``shard_span_ptrs``: k*T entries, row-major (entry s*T + t = span t of shard s)."""
     _check(_load().reft_parity_encode(plan, ptr_array(shard_span_ptrs), int(k), _addr(parity_dev),
                                       _stream(stream)))
+
+
+def reft_parity_encode_pack(plan, shard_span_ptrs, k: int, own: int, parity_dev, packed_dev,
+                            stream=None, packed_cap: Optional[int] = None) -> None:
+    _check(_load().reft_parity_encode_pack(plan, ptr_array(shard_span_ptrs), int(k), int(own),
+                                           _addr(parity_dev), _addr(packed_dev),
+                                           _nbytes(packed_dev) if packed_cap is None else int(packed_cap),
+                                           _stream(stream)))
 
 
 def reft_parity_encode_noalloc(plan, shard_span_ptrs, k: int, parity_dev, stream=None) -> None:

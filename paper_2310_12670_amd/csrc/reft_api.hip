@@ -1468,6 +1468,60 @@ extern "C" int reft_parity_encode(reft_plan *p, const void *const *shard_span_pt
     REFT_GUARD_END("reft_parity_encode")
 }
 
+// S1 + S4 in one pass: the parity of the k shards and the packed stream of shard `own`.
+extern "C" int reft_parity_encode_pack(reft_plan *p, const void *const *shard_span_ptrs, uint32_t k,
+                                       uint32_t own, void *parity_dev, void *packed_dev,
+                                       uint64_t packed_cap, reft_stream stream)
+{
+    REFT_GUARD_BEGIN
+    int rc = check_plan(p, "reft_parity_encode_pack");
+    if (rc) return rc;
+    if (k < 1 || k > REFT_MAX_K)
+        return fail(REFT_EINVAL, "reft_parity_encode_pack: k = %u outside [1, %d]", k, REFT_MAX_K);
+    if (own >= k) return fail(REFT_EINVAL, "reft_parity_encode_pack: own = %u but k = %u", own, k);
+    if ((rc = check_span_ptrs(p, shard_span_ptrs, k, "reft_parity_encode_pack"))) return rc;
+    if (packed_cap < p->L) return fail(REFT_ESIZE, "reft_parity_encode_pack: packed buffer too small");
+    if (p->L == 0) return REFT_OK;
+    if (!parity_dev || !packed_dev)
+        return fail(REFT_EINVAL, "reft_parity_encode_pack: null parity or packed buffer");
+    hipStream_t s = (hipStream_t)stream;
+    const uint64_t T = p->T;
+    // the own shard's row first: the fused kernel packs the first row it reads
+    const void **rows = p->row_buf.data();
+    std::copy(shard_span_ptrs + (size_t)own * T, shard_span_ptrs + (size_t)(own + 1) * T, rows);
+    for (uint32_t j = 0, r = 1; j < k; ++j)
+        if (j != own) {
+            std::copy(shard_span_ptrs + (size_t)j * T, shard_span_ptrs + (size_t)(j + 1) * T,
+                      rows + (size_t)r * T);
+            ++r;
+        }
+    const LaunchCfg cfg = launch_cfg(p);
+    const uint64_t vb = (uint64_t)(uintptr_t)parity_dev, vb2 = (uint64_t)(uintptr_t)packed_dev;
+    const uint64_t stage = g_burst_stage.load();
+    // The fused kernel applies where the burst kernel does (rows, bytes, no tiles dense in small
+    // spans), in one pass of at most kMaxSrc rows, with both destinations aligned alike and its
+    // one instantiation per row count (unroll 4, non-temporal); its two LDS images per half must
+    // fit a compute unit's LDS.  Otherwise: the encode and the pack as two launches.
+    const bool fused = g_burst.load() && p->L >= g_burst_min_bytes.load() && k <= (uint32_t)kMaxSrc &&
+                       k >= g_burst_min_rows.load() && dense_tiles(p, cfg.small_pieces) * 100 <= p->ntiles &&
+                       ((vb ^ vb2) & 15u) == 0 && cfg.unroll == 4 && cfg.nontemporal &&
+                       4 * (stage + 16) + 16 <= 160 * 1024;
+    const uint64_t *tab = nullptr;
+    int entry = 0;
+    if ((rc = upload_ptrs(p, rows, k, s, &tab, &entry))) return rc;
+    if (fused) {
+        const BurstCfg bc = burst_cfg(p->burst_ctr, p->burst_next++ % kCtrBlocks, p->num_cus);
+        HIPCHK(launch_gather_burst_pack(p->tables(), tab, (int)k, vb, vb2, 0, p->L, cfg, bc, s));
+    } else {
+        if ((rc = xor_passes(p, tab, k, nullptr, nullptr, parity_dev, p->burst_ctr, kCtrBlocks,
+                             &p->burst_next, s)))
+            return rc;
+        HIPCHK(launch_gather(p->tables(), tab, 1, false, nullptr, vb2, 0, p->L, cfg, s));
+    }
+    return release_ptrs(p, entry, s);
+    REFT_GUARD_END("reft_parity_encode_pack")
+}
+
 // ------------------------------------------------------------------------------------------------
 // S4 for callers that cannot allocate
 // ------------------------------------------------------------------------------------------------

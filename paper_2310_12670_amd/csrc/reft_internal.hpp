@@ -61,6 +61,13 @@ hipError_t launch_gather_burst(const PlanTables &pt, const uint64_t *tab, int nr
                                const uint64_t *dtab, uint64_t vb, uint64_t lo, uint64_t hi,
                                const LaunchCfg &cfg, const BurstCfg &bc, hipStream_t stream);
 
+// Fused pack + encode: the parity of the nrows rows (contiguous, virtual base vb) and, in the same
+// pass, the packed stream of row 0 (contiguous, virtual base vb2, congruent to vb modulo 16).
+// The kernel keeps two LDS images per half: 4 * (stage_bytes + 16) bytes per workgroup.
+hipError_t launch_gather_burst_pack(const PlanTables &pt, const uint64_t *tab, int nrows, uint64_t vb,
+                                    uint64_t vb2, uint64_t lo, uint64_t hi, const LaunchCfg &cfg,
+                                    const BurstCfg &bc, hipStream_t stream);
+
 // src_vbase + o is the source address of stream byte o; tab is one row of T span pointers.
 hipError_t launch_scatter(const PlanTables &pt, const uint64_t *tab, uint64_t src_vbase,
                           uint64_t lo, uint64_t hi, const LaunchCfg &cfg, hipStream_t stream);

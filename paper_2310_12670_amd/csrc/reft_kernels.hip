@@ -105,15 +105,27 @@ struct ToImage {
     __device__ __forceinline__ void put8(uint64_t a, uint8_t v) const { img[(uint32_t)(a - origin)] = v; }
 };
 
+// The absent second destination of a piece (see xor_piece).
+struct NoSink {
+    static constexpr bool kActive = false;
+    template <bool NT>
+    __device__ __forceinline__ void put16(uint64_t, u32x4) const {}
+    __device__ __forceinline__ void put8(uint64_t, uint8_t) const {}
+};
+
 // One piece: n bytes at destination address d = XOR of the n bytes at each source address s[j].
 // The whole workgroup cooperates.  Destination stores are 16-byte aligned: up to 15 head bytes
 // and 15 tail bytes are moved bytewise, the body as 16-byte chunks.  If every source is
 // co-aligned with the destination (the case for tensors whose sizes and addresses are multiples
 // of 16) the body is plain vector loads, U chunks in flight per thread and source; otherwise each
 // misaligned source is read as two aligned chunks and byte-shifted in registers.
-template <int K, int U, bool NT, class Sink = ToGlobal>
+// With a second sink, the bytes of the first source alone also go to address d2 (+ the same
+// offsets) of that sink: the packed copy of one shard beside the parity of all.  d2 must be
+// congruent to d modulo 16.
+template <int K, int U, bool NT, class Sink = ToGlobal, class Sink2 = NoSink>
 __device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], uint32_t n,
-                                          const Sink sink = Sink())
+                                          const Sink sink = Sink(), uint64_t d2 = 0,
+                                          const Sink2 sink2 = Sink2())
 {
     const uint32_t tid = threadIdx.x;
     uint32_t head = (uint32_t)(0 - d) & 15u;
@@ -128,6 +140,7 @@ __device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], ui
         else if (tid >= 16 && tid - 16 < tail) i = head + (nb << 4) + (tid - 16);
         if (i != 0xffffffffu) {
             uint8_t v = ld8(s[0] + i);
+            sink2.put8(d2 + i, v);
 #pragma unroll
             for (int j = 1; j < K; ++j) v ^= ld8(s[j] + i);
             sink.put8(d + i, v);
@@ -136,6 +149,7 @@ __device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], ui
     if (nb == 0) return;
 
     const uint64_t da = d + head;
+    const uint64_t da2 = d2 + head;
     uint32_t mis = 0;
 #pragma unroll
     for (int j = 0; j < K; ++j) mis |= (uint32_t)(s[j] + head) & 15u;
@@ -151,6 +165,9 @@ __device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], ui
 #pragma unroll
             for (int u = 0; u < U; ++u) v[u] = ld16<NT>(sp[0] + c + u * kThreads);
 #pragma unroll
+            for (int u = 0; u < U; ++u)
+                sink2.template put16<NT>(da2 + ((uint64_t)(c + u * kThreads) << 4), v[u]);
+#pragma unroll
             for (int j = 1; j < K; ++j) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) v[u] ^= ld16<NT>(sp[j] + c + u * kThreads);
@@ -161,6 +178,7 @@ __device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], ui
         }
         for (uint32_t c = full + tid; c < nb; c += kThreads) {
             u32x4 v = ld16<NT>(sp[0] + c);
+            sink2.template put16<NT>(da2 + ((uint64_t)c << 4), v);
 #pragma unroll
             for (int j = 1; j < K; ++j) v ^= ld16<NT>(sp[j] + c);
             sink.template put16<NT>(da + ((uint64_t)c << 4), v);
@@ -168,6 +186,7 @@ __device__ __forceinline__ void xor_piece(uint64_t d, const uint64_t (&s)[K], ui
     } else {
         for (uint32_t c = tid; c < nb; c += kThreads) {
             u32x4 v = load_any<NT>(s[0] + head, c);
+            sink2.template put16<NT>(da2 + ((uint64_t)c << 4), v);
 #pragma unroll
             for (int j = 1; j < K; ++j) v ^= load_any<NT>(s[j] + head, c);
             sink.template put16<NT>(da + ((uint64_t)c << 4), v);
@@ -460,7 +479,8 @@ __device__ __forceinline__ void emit_piece(uint64_t d, REFT_LDS const unsigned c
 
 // The rounds of a burst kernel.  read(st, img) is run by the 256 reader threads and puts stage st
 // into the LDS image at img; emit(st, img, lane) is run by the writer wave and stores the image.
-template <class Read, class Emit>
+// With NIMG = 2 every half holds a second image behind the two of the first (at + 2 * (stage + 16)).
+template <int NIMG = 1, class Read, class Emit>
 __device__ __forceinline__ void burst_rounds(uint64_t nstages, uint32_t stage, uint32_t *ctr,
                                              uint32_t max_polls, uint32_t nap, Read read, Emit emit)
 {
@@ -476,7 +496,7 @@ __device__ __forceinline__ void burst_rounds(uint64_t nstages, uint32_t stage, u
     uint32_t skip = 0, backoff = 0;                    // writer wave: rounds left without waiting
     // writer wave, lane 0: how its rounds went (met, timed out, not waited), kept in LDS behind
     // the two images so that the bookkeeping costs the kernels no registers
-    REFT_LDS uint32_t *tally = (REFT_LDS uint32_t *)(lds + 2 * half);
+    REFT_LDS uint32_t *tally = (REFT_LDS uint32_t *)(lds + 2 * NIMG * half);
     if (threadIdx.x == kThreads) tally[0] = tally[1] = tally[2] = 0;
 
     for (uint64_t r = 0; r <= rounds; ++r) {
@@ -583,6 +603,48 @@ k_gather_burst(PlanTables pt, const uint64_t *__restrict__ tab, const uint64_t *
                     o = pe;
                 }
             }
+        });
+}
+
+// The parity of K rows into a contiguous destination and, in the same pass, the packed stream of
+// row 0 into a second contiguous destination (fused pack + encode: the first row is read once
+// for both).  vb2 is the virtual base of the packed copy, congruent to vb modulo 16.  Two LDS
+// images per half, so a workgroup needs 4 * (stage + 16) bytes of LDS.
+template <int K, int U, bool NT>
+__global__ void __launch_bounds__(kBurstThreads)
+k_gather_burst_pack(PlanTables pt, const uint64_t *__restrict__ tab, uint64_t vb, uint64_t vb2,
+                    uint64_t lo, uint64_t hi, uint32_t stage, uint32_t *ctr, uint32_t max_polls,
+                    uint32_t nap)
+{
+    const uint64_t nstages = (hi - lo + stage - 1) / stage;
+    const uint32_t second = 2 * (stage + 16);          // the second image of a half
+    burst_rounds<2>(
+        nstages, stage, ctr, max_polls, nap,
+        [&](uint64_t st, REFT_LDS unsigned char *img) {
+            uint64_t o = lo + st * stage;
+            uint64_t e = o + stage;
+            if (e > hi) e = hi;
+            const ToImage sink{img, (vb + o) & ~15ull};
+            const ToImage sink2{img + second, (vb2 + o) & ~15ull};
+            uint32_t i = pt.first_span[o >> pt.tile_shift];
+            while (o < e) {
+                while (pt.off[i + 1] <= o) ++i;        // o < e <= L = off[T]
+                const uint64_t so = pt.off[i];
+                uint64_t pe = pt.off[i + 1];
+                if (pe > e) pe = e;
+                uint64_t s[K];
+#pragma unroll
+                for (int j = 0; j < K; ++j) s[j] = tab[(uint64_t)j * pt.T + i] + (o - so);
+                xor_piece<K, U, NT, ToImage, ToImage>(vb + o, s, (uint32_t)(pe - o), sink, vb2 + o,
+                                                      sink2);
+                o = pe;
+            }
+        },
+        [&](uint64_t st, REFT_LDS const unsigned char *img, uint32_t lane) {
+            const uint64_t o = lo + st * stage;
+            const uint64_t e = o + stage < hi ? o + stage : hi;
+            emit_piece<NT>(vb + o, img + ((uint32_t)(vb + o) & 15u), (uint32_t)(e - o), lane);
+            emit_piece<NT>(vb2 + o, img + second + ((uint32_t)(vb2 + o) & 15u), (uint32_t)(e - o), lane);
         });
 }
 
@@ -742,9 +804,10 @@ static bool burst_cfg_ok(const BurstCfg &bc)
 
 // Grid of a burst launch: every workgroup resident at once.
 static hipError_t burst_grid(const void *fn, uint64_t nstages, const LaunchCfg &cfg,
-                             const BurstCfg &bc, size_t *lds, uint32_t *grid)
+                             const BurstCfg &bc, size_t *lds, uint32_t *grid, int images = 1)
 {
-    *lds = 2 * ((size_t)bc.stage_bytes + 16) + 16;      // two images and the writer's tally
+    // one image per half (two with the fused pack) and the writer's tally
+    *lds = 2 * (size_t)images * ((size_t)bc.stage_bytes + 16) + 16;
     int per_cu = 0;
     hipError_t e = burst_occupancy(fn, *lds, &per_cu);
     if (e != hipSuccess) return e;
@@ -775,6 +838,37 @@ hipError_t launch_gather_burst(const PlanTables &pt, const uint64_t *tab, int nr
     hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(256), 0, stream, bc.ctr, 9 * kCtrStride);
     hipLaunchKernelGGL(fn, dim3(grid), dim3(kBurstThreads), lds, stream, pt, tab, dtab, vb, lo, hi,
                        acc ? 1u : 0u, bc.stage_bytes, bc.ctr, bc.max_polls, bc.nap);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_burst_pack(const PlanTables &pt, const uint64_t *tab, int nrows, uint64_t vb,
+                                    uint64_t vb2, uint64_t lo, uint64_t hi, const LaunchCfg &cfg,
+                                    const BurstCfg &bc, hipStream_t stream)
+{
+    if (lo >= hi) return hipSuccess;
+    if (hi > pt.L || !burst_cfg_ok(bc) || ((vb ^ vb2) & 15u)) return hipErrorInvalidValue;
+    if (4 * ((size_t)bc.stage_bytes + 16) + 16 > 160 * 1024) return hipErrorInvalidValue;
+    void (*fn)(PlanTables, const uint64_t *, uint64_t, uint64_t, uint64_t, uint64_t, uint32_t,
+               uint32_t *, uint32_t, uint32_t) = nullptr;
+    switch (nrows) {                                   // one instantiation per row count
+    case 1: fn = k_gather_burst_pack<1, 4, true>; break;
+    case 2: fn = k_gather_burst_pack<2, 4, true>; break;
+    case 3: fn = k_gather_burst_pack<3, 4, true>; break;
+    case 4: fn = k_gather_burst_pack<4, 4, true>; break;
+    case 5: fn = k_gather_burst_pack<5, 4, true>; break;
+    case 6: fn = k_gather_burst_pack<6, 4, true>; break;
+    case 7: fn = k_gather_burst_pack<7, 4, true>; break;
+    case 8: fn = k_gather_burst_pack<8, 4, true>; break;
+    default: return hipErrorInvalidValue;
+    }
+    size_t lds = 0;
+    uint32_t grid = 0;
+    const uint64_t nstages = (hi - lo + bc.stage_bytes - 1) / bc.stage_bytes;
+    hipError_t e = burst_grid((const void *)fn, nstages, cfg, bc, &lds, &grid, 2);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(256), 0, stream, bc.ctr, 9 * kCtrStride);
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(kBurstThreads), lds, stream, pt, tab, vb, vb2, lo, hi,
+                       bc.stage_bytes, bc.ctr, bc.max_polls, bc.nap);
     return hipGetLastError();
 }
 

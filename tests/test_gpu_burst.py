@@ -326,3 +326,71 @@ def test_burst_statistics_add_up(dev):
                 assert groups >= 1
     finally:
         reft.reft_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("k", [1, 2, 5, 8, 11])
+@pytest.mark.parametrize("phases", ["alike", "apart"])
+def test_fused_pack_and_encode(dev, k, phases):
+    """reft_parity_encode_pack: parity of k shards and the packed stream of each shard in turn,
+    against the oracle; ragged sizes, misaligned sources; destinations aligned alike (single pass
+    where k <= 8) and apart (two launches), canaries around both."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(500 + k)
+    rng = np.random.default_rng(k)
+    sizes = [3 << 20, 12345, 0, 1 << 20, 17, (2 << 20) + 3, 65536]
+    L = sum(sizes)
+    shards, keep = [], []
+    for s in range(k):
+        arena, spans = spans_in_arena(sizes, [int(x) for x in rng.integers(0, 16, size=len(sizes))], dev, gen)
+        keep.append(arena)
+        shards.append(spans)
+    streams = [oracle.pack([oracle.as_bytes(t.cpu()) for t in sh]) for sh in shards]
+    want = oracle.encode(streams)
+    plan = reft.reft_plan_create(sizes)
+    try:
+        for own in sorted({0, k // 2, k - 1}):
+            ph_a = int(rng.integers(0, 16))
+            ph_b = ph_a if phases == "alike" else (ph_a + 1 + int(rng.integers(0, 15))) % 16
+            ra = torch.full((L + 2 * GUARD + ph_a,), CANARY, dtype=torch.uint8, device=dev)
+            rb = torch.full((L + 2 * GUARD + ph_b,), CANARY, dtype=torch.uint8, device=dev)
+            par, pk = ra[GUARD + ph_a:GUARD + ph_a + L], rb[GUARD + ph_b:GUARD + ph_b + L]
+            reft.reft_parity_encode_pack(plan, [t for sh in shards for t in sh], k, own, par, pk)
+            torch.cuda.synchronize()
+            a, b = ra.cpu().numpy(), rb.cpu().numpy()
+            assert np.array_equal(a[GUARD + ph_a:GUARD + ph_a + L], want), (k, own, "parity")
+            assert np.array_equal(b[GUARD + ph_b:GUARD + ph_b + L], streams[own]), (k, own, "packed")
+            assert np.all(a[:GUARD + ph_a] == CANARY) and np.all(a[GUARD + ph_a + L:] == CANARY)
+            assert np.all(b[:GUARD + ph_b] == CANARY) and np.all(b[GUARD + ph_b + L:] == CANARY)
+        with pytest.raises(reft.ReftError) as e:
+            reft.reft_parity_encode_pack(plan, [t for sh in shards for t in sh], k, k, par, pk)
+        assert e.value.code == reft.REFT_EINVAL
+        with pytest.raises(reft.ReftError) as e:
+            reft.reft_parity_encode_pack(plan, [t for sh in shards for t in sh], k, 0, par, pk, packed_cap=L - 1)
+        assert e.value.code == reft.REFT_ESIZE
+    finally:
+        reft.reft_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("stage,wgs", [(4096, 2), (12288, 1), (36864, 2), (40960, 2)])
+def test_fused_pack_and_encode_stage_sizes(dev, stage, wgs):
+    """Stage sizes up to the largest whose two images fit the LDS, and one beyond (two launches)."""
+    reft.reft_set_tunable("burst_stage_bytes", stage)
+    reft.reft_set_tunable("burst_wgs_per_cu", wgs)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(stage)
+    sizes = [(5 << 20) + 48, 4096, 999]
+    L, k = sum(sizes), 6
+    shards = [[torch.randint(0, 256, (n,), dtype=torch.uint8, device=dev, generator=gen) for n in sizes]
+              for _ in range(k)]
+    streams = [oracle.pack([oracle.as_bytes(t.cpu()) for t in sh]) for sh in shards]
+    plan = reft.reft_plan_create(sizes)
+    try:
+        par = torch.empty(L, dtype=torch.uint8, device=dev)
+        pk = torch.empty(L, dtype=torch.uint8, device=dev)
+        for rep in range(3):                      # back to back on one plan
+            reft.reft_parity_encode_pack(plan, [t for sh in shards for t in sh], k, 2, par, pk)
+        torch.cuda.synchronize()
+        assert np.array_equal(par.cpu().numpy(), oracle.encode(streams))
+        assert np.array_equal(pk.cpu().numpy(), streams[2])
+    finally:
+        reft.reft_plan_destroy(plan)

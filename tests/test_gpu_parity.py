@@ -148,6 +148,17 @@ def run_case(dev, shards, sizes, buckets=None, uniform=0, lost=None, nslots=2, o
         assert np.array_equal(par.bytes(), parity_ref), "parity_encode"
         par.check("parity_encode")
 
+        # S1+S4 fused: the parity again, and the packed stream of one shard, in one call
+        own = k - 1 if lost is None else lost
+        par2 = Guarded(L, dev, phase=out_phase)
+        pk2 = Guarded(L, dev, phase=out_phase if seed % 2 == 0 else (out_phase + 5) % 16)
+        reft.reft_parity_encode_pack(plan, flat, k, own, par2.view, pk2.view, s1, packed_cap=L)
+        s1.synchronize()
+        assert np.array_equal(par2.bytes(), parity_ref), "parity_encode_pack: parity"
+        assert np.array_equal(pk2.bytes(), streams[own]), "parity_encode_pack: packed stream"
+        par2.check("parity_encode_pack (parity)")
+        pk2.check("parity_encode_pack (packed)")
+
         # S6: decode the lost shard(s) from the packed survivors and the parity
         for j in (range(k) if lost is None else [lost]):
             out = Guarded(L, dev, phase=out_phase)
