@@ -724,6 +724,9 @@ def has_demo(b, iterations=5):
              floor(n * t_bubble / t_ss) (SplitParameter), sent with the direct transport at full
              link rate; layer 2: the remaining buckets and the parity go out beside the burst with
              the staged transport (DMA copies, no kernels).
+      fused  in the bubble only one kernel: pack + encode in one pass (reft_parity_encode_pack)
+             into a packed device copy of the shard and the parity; beside the burst two large
+             DMA copies (packed shard, parity).  Needs L more bytes of device memory and no cut.
 
     t_ss = size / B_io (EstimateSnapshotTime) with B_io measured here; the bubble length is an
     input (the printed EstimateBubbleTime formula is not used)."""
@@ -763,8 +766,13 @@ def has_demo(b, iterations=5):
         s_snap.wait_stream(s_xor)
         reft.reft_snapshot_pack(pplan, b.p_par, b.stag_psave, b.host_par, s_snap, s_copy)
 
+    packed = torch.empty(L, dtype=torch.uint8, device=b.dev)
+    p_packed = reft.ptr_array([packed])
+
     def iteration(policy):
         t_start = time.perf_counter()
+        if policy == "fused":
+            reft.reft_parity_encode_pack(plan, b.p_all, k, b.own, b.parity, packed, s_xor)
         if policy == "has":                      # layer 1: the bubble
             reft.reft_parity_encode(plan, b.p_all, k, b.parity, s_xor)
             reft.reft_snapshot_pack_range(plan, b.p_own, None, b.host_snap, 0, b_cut, s_snap, None)
@@ -777,13 +785,17 @@ def has_demo(b, iterations=5):
             reft.reft_snapshot_pack_range(plan, b.p_own, b.stag_save, b.host_snap, b_cut, nb, s_snap, s_copy)
             s_snap.wait_stream(s_xor)
             reft.reft_snapshot_pack(pplan, b.p_par, b.stag_psave, b.host_par, s_snap, s_copy)
+        elif policy == "fused":                  # beside compute: two large copies
+            s_snap.wait_stream(s_xor)
+            reft.reft_snapshot_pack(pplan, p_packed, b.stag_psave, b.host_snap, s_snap, s_copy)
+            reft.reft_snapshot_pack(pplan, b.p_par, b.stag_psave, b.host_par, s_snap, s_copy)
         done.synchronize()
         t_compute_done = time.perf_counter()
         torch.cuda.synchronize()                 # the snapshot must have landed before the next one
         return t_compute_done - t_start, time.perf_counter() - t_start
 
     out = {}
-    for policy in ("none", "naive", "has", "none", "naive", "has"):
+    for policy in ("none", "naive", "has", "fused", "none", "naive", "has", "fused"):
         iteration(policy)                        # warm-up
         its = [iteration(policy) for _ in range(iterations)]
         med = sorted(x[0] for x in its)[len(its) // 2]
@@ -791,6 +803,10 @@ def has_demo(b, iterations=5):
         out.setdefault(policy, []).append((med, full))
     res = {p: (min(v[0][0], v[1][0]), min(v[0][1], v[1][1])) for p, v in out.items()}
     base = res["none"][0]
+    # the fused policy's host copies are what the ordinary snapshot gives (device-side comparison)
+    want = torch.cat([t.reshape(-1).view(torch.uint8) for t in b.shards[b.own]])
+    fused_ok = bool(torch.equal(b.host_snap.to(b.dev), want)) and bool(torch.equal(b.host_par.to(b.dev), b.parity))
+    del want, packed
     return {
         "metric": "iteration time of a synthetic pipeline stage with one snapshot per iteration",
         "workload": f"config {b.wl.cfg}",
@@ -800,6 +816,7 @@ def has_demo(b, iterations=5):
         "iteration_ms": {p: round(v[0] * 1e3, 2) for p, v in res.items()},
         "iteration_plus_snapshot_tail_ms": {p: round(v[1] * 1e3, 2) for p, v in res.items()},
         "overhead_pct": {p: round(100.0 * (v[0] - base) / base, 2) for p, v in res.items()},
+        "fused_snapshot_verified": fused_ok,
     }
 
 
