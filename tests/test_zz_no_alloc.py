@@ -114,3 +114,35 @@ def test_noalloc_encode_rejects_what_the_scratch_cannot_hold(dev):
         assert e.value.code == reft.REFT_EINVAL
     finally:
         reft.reft_plan_destroy(plan)
+
+
+def test_noalloc_encode_replays_in_a_hip_graph(dev):
+    """Captured into a HIP graph once (the call allocates nothing and clears its counters with a
+    kernel, not a memset node) and replayed four times, the tensors' contents changed and eager
+    work and synchronisations between the replays: every replay gives the oracle's parity of the
+    current contents."""
+    k, sizes = 8, sizes_for((9 << 20) + 5, 12, 9)
+    L = sum(sizes)
+    shards = make_shards(dev, k, sizes, 41)
+    flat = [t for sh in shards for t in sh]
+    plan = reft.reft_plan_create(sizes, None, 0)
+    try:
+        out = torch.empty(L, dtype=torch.uint8, device=dev)
+        s = torch.cuda.Stream()
+        reft.reft_parity_encode_noalloc(plan, flat, k, out, s)      # first use outside the capture
+        s.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=s):
+            reft.reft_parity_encode_noalloc(plan, flat, k, out, torch.cuda.current_stream())
+        for rep in range(4):
+            for t in flat[rep::5]:
+                t.add_(rep + 1)                                      # new contents, same addresses
+            out.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            want = oracle.encode([oracle.pack([oracle.as_bytes(t.cpu()) for t in sh]) for sh in shards])
+            assert np.array_equal(out.cpu().numpy(), want), f"replay {rep}"
+        del graph
+    finally:
+        reft.reft_plan_destroy(plan)
