@@ -201,7 +201,7 @@ class Bench:
     def reset_pipeline(self):
         self.n = 0
         self.ev = {name: {} for name in ("shard_saved", "par_saved", "shard_restored",
-                                         "par_restored", "decoded")}
+                                         "par_restored", "decoded", "window_closed")}
 
     def _mark(self, name, n, stream):
         e = self.torch.cuda.Event()
@@ -301,7 +301,11 @@ class Bench:
             if n >= 2:
                 self._decode(n - 2, timed)          # the XOR window: encode(n), decode(n-2)
             if n >= 1:
-                self._restore_parity(n - 1)         # beside this step's shard snapshot
+                # beside this step's shard snapshot, and behind the window also in the first steps,
+                # where no decode holds it back yet
+                self._mark("window_closed", n, self.s_save)
+                self._wait(self.s_load, "window_closed", n)
+                self._restore_parity(n - 1)
             self._snapshot_shard(n)
             self._snapshot_parity(n)
             self._restore_shard(n)                  # beside this step's parity snapshot
@@ -311,6 +315,7 @@ class Bench:
         """Queue what the pipeline still owes after the last step."""
         n = self.n
         if not self.args.serial and n >= 1:
+            self._wait(self.s_save, "shard_restored", n - 1)      # the last window, as in step()
             if n >= 2:
                 self._decode(n - 2, timed)
             self._restore_parity(n - 1)
