@@ -166,6 +166,20 @@ def run_full(dev, cfg, do_reconstruct, with_gemm=False):
         assert torch.equal(host_par.to(dev), parity)
         say("full-size properties ok (host == tensors, zero-sum, parity snapshot)")
 
+        # -- pack + encode in one pass, as bench.py's stage runs it: same parity, and the packed
+        #    stream of the own shard (oracle windows; every byte against the host snapshot)
+        par_f = torch.empty(L, dtype=torch.uint8, device=dev)
+        packed = torch.empty(L, dtype=torch.uint8, device=dev)
+        reft.reft_parity_encode_pack(plan, [t for sh in shards for t in sh], k, own, par_f, packed, s_xor)
+        s_xor.synchronize()
+        for (a, b), (p, win) in par_ref.items():
+            assert np.array_equal(par_f[a:b].cpu().numpy(), p), f"fused parity window [{a},{b})"
+            assert np.array_equal(packed[a:b].cpu().numpy(), win[own]), f"fused packed window [{a},{b})"
+        assert torch.equal(par_f, parity), "fused parity"
+        assert torch.equal(packed, host.to(dev)), "fused packed stream"
+        del par_f, packed
+        say("pack + encode in one pass ok")
+
         # -- load phase, once with each transport (bench.py times the staged one): restore of the
         #    own shard and of the parity, oracle windows on the restored tensors, every byte with torch
         lstaging = torch.empty(nslots * slot, dtype=torch.uint8, device=dev)
