@@ -32,7 +32,9 @@
  *     rotated call for a given (k, member) only.  The data-moving calls allocate none and never
  *     wait for the whole device; they block the calling thread only in one case: a call that
  *     brings a pointer array the plan has not seen lately may have to wait for the kernels that
- *     still read the cached table whose room it takes (see reft_plan_create).
+ *     still read the cached table whose room it takes (see reft_plan_create).  (The optional
+ *     transports "dma_streams" = 2 and "graph_copies" make a helper stream / a graph on the first
+ *     call that uses them.)
  *   - The data-moving calls enqueue work on the given streams and return; results are complete
  *     when those streams (or reft_snapshot_wait / reft_restore_wait) have been synchronised.
  *     Source data must not be modified, and pointer arrays' targets not freed, before that.
@@ -55,7 +57,7 @@ extern "C" {
 #define REFT_ESIZE          (-2)  /* a buffer is too small or a length does not match the plan    */
 #define REFT_EHIP           (-3)  /* a HIP runtime call failed; text in reft_last_error()         */
 #define REFT_EUNRECOVERABLE (-4)  /* more than one shard lost: beyond what one parity can decode  */
-#define REFT_EBUSY          (-5)  /* the previous snapshot of a reft_ckpt has not been committed yet */
+#define REFT_EBUSY          (-5)  /* reft_ckpt_begin while an earlier commit has not landed yet      */
 
 #define REFT_MAX_K 32             /* most shards (or survivors + parity) in one call              */
 
