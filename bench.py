@@ -914,4 +914,8 @@ def cpu_baseline(wl, shards, own, lost, sample_bytes):
 
 
 if __name__ == "__main__":
-    sys.exit(main())
+    # (no sys.exit on success: with rocprofv3's memory-copy trace attached, leaving through
+    # SystemExit ends in a crash inside the tool's own finalization)
+    status = main()
+    if status:
+        sys.exit(status)
