@@ -74,11 +74,14 @@ def parse_args():
                     help="no pipelining across steps: a step's save starts when the previous "
                          "step's load has ended")
     ap.add_argument("--queue-depth", type=int, default=1, choices=[1, 2, 3],
-                    help="before queuing a step the host waits for the parity snapshot of the step "
-                         "this many steps back (default 1).  A trainer takes one snapshot per "
-                         "iteration; with two or three steps' copies queued ahead (some 4000 "
-                         "hipMemcpyAsync calls) the runtime's device-to-host copies drop to a "
-                         "quarter of their rate")
+                    help="before queuing a step the host waits until the parity snapshot or the "
+                         "shard restore of the step this many steps back has ended, whichever "
+                         "comes first (default 1).  The runtime picks a copy engine for a stream "
+                         "when its copies are queued: with the link idle at that moment the two "
+                         "directions can land on one engine and run one after the other, and with "
+                         "two or three steps' copies queued ahead (some 4000 hipMemcpyAsync calls) "
+                         "the choice climbs to engines that move host traffic at a quarter of the "
+                         "rate")
     ap.add_argument("--trace-phases", action="store_true",
                     help="log when each phase of each timed step began and ended (HIP events)")
     ap.add_argument("--gemm-seconds", type=float, default=0.0,
@@ -201,7 +204,7 @@ class Bench:
     def reset_pipeline(self):
         self.n = 0
         self.ev = {name: {} for name in ("shard_saved", "par_saved", "shard_restored",
-                                         "par_restored", "decoded", "window_closed")}
+                                         "par_restored", "decoded", "window_closed", "load_turn")}
 
     def _mark(self, name, n, stream):
         e = self.torch.cuda.Event()
@@ -280,12 +283,41 @@ class Bench:
             self.pplan, self.host_par, self.stag_pload, self.p_par2, self.s_load, self.s_load))
         self._mark("par_restored", n, self.s_load)
 
+    def _pace(self, n):
+        """Host-side pacing: queue step n once one of the two copy streams has finished step
+        n - queue_depth and the other is still busy with it.
+
+        Why this moment (read from the runtime's own log, AMD_LOG_LEVEL=4): a stream's copies go to
+        the lowest-numbered copy engine that has nothing pending at the time the stream chooses, and
+        a stream chooses again only when it waits for another stream right behind its copies.  If
+        both streams are idle when a step is queued (which happens once, in the second step after
+        a start, where the parity snapshot outlasts the shard restore), the load stream takes the
+        save stream's engine, the save stream keeps it, and each phase's piece copies run only
+        after the other direction's 15 GB copy (530 ms instead of 300, twice).  With one of the two
+        still busy the choices never collide.  Queuing earlier is no remedy: with more copies
+        pending the choice climbs to engines 0x10 and 0x20, which moved host traffic at 13 and
+        24 GB/s instead of 56."""
+        a = self.ev["par_saved"].get(n - self.args.queue_depth)
+        b = self.ev["shard_restored"].get(n - self.args.queue_depth)
+        if a is None or b is None:
+            return
+        while not (a.query() or b.query()):
+            time.sleep(100e-6)
+
+    def _rechoose_engine(self, n):
+        """Make the save stream wait, through the load stream, for its own shard snapshot.
+
+        The wait orders nothing new; it is there because a stream keeps its copy engine until a
+        wait for another stream has come true (see _pace).  Step 0 has no such wait on the save
+        stream, so in step 1 the save stream would still sit on the engine that the load stream,
+        choosing again with everything idle, has just taken."""
+        self._wait(self.s_load, "shard_saved", n)
+        self._mark("load_turn", n, self.s_load)
+        self._wait(self.s_save, "load_turn", n)
+
     def step(self, timed=False):
         n = self.n
-        # host-side pacing (see --queue-depth)
-        old = self.ev["par_saved"].get(n - self.args.queue_depth)
-        if old is not None:
-            old.synchronize()
+        self._pace(n)
         # The XOR window opens when the previous step's shard restore has ended (the next snapshot
         # needs its host buffer read anyway): DMA writes trickling into HBM beside the XOR kernels
         # cost them 5 % (measured), and nothing else is in flight at this point.
@@ -307,6 +339,7 @@ class Bench:
                 self._wait(self.s_load, "window_closed", n)
                 self._restore_parity(n - 1)
             self._snapshot_shard(n)
+            self._rechoose_engine(n)
             self._snapshot_parity(n)
             self._restore_shard(n)                  # beside this step's parity snapshot
         self.n = n + 1

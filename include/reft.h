@@ -138,9 +138,14 @@ int reft_plan_staged_work(reft_plan *plan, uint64_t *gather_launches, uint64_t *
  * A snapshot and a restore only overlap on the link (full duplex) if their copy streams sit on
  * different queues: give each its own stream, created early, and keep the process's stream count
  * low (when reft_plan_staged_work reports no gather launches, one stream serves as pack_stream
- * and copy_stream).  Queue depth: with several snapshots' copies queued ahead (thousands of
- * hipMemcpyAsync calls) the runtime's device-to-host copies run at a fraction of their rate; wait
- * for the previous snapshot (reft_snapshot_wait, an event) before queuing the next.
+ * and copy_stream).  Copy engines: the runtime gives a stream's copies to the lowest-numbered copy
+ * engine with nothing pending when the stream chooses, and the stream keeps it until a wait for
+ * another stream's event has come true.  Two consequences, both measured: with several snapshots'
+ * copies queued ahead (thousands of hipMemcpyAsync calls) the choice reaches engines that move
+ * host traffic at a quarter of the rate, so wait for the previous snapshot (reft_snapshot_wait, an
+ * event) before queuing the next; and a restore queued while nothing is in flight can be given
+ * the engine that the snapshot stream still holds, after which the two directions take turns
+ * instead of overlapping: queue one direction while the other still has copies pending.
  * After the last bucket a completion event is recorded (see reft_snapshot_wait): the snapshot is
  * complete only when every bucket has landed (section 4.4: COMPLETED when all tensors are
  * snapshotted).  Postcondition: host_dst[0..L) == stream; host_dst[L..) untouched.

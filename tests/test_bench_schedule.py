@@ -20,6 +20,9 @@ class FakeEvent:
     def synchronize(self):
         pass
 
+    def query(self):
+        return True
+
 
 class FakeStream:
     def __init__(self, name):
