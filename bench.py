@@ -82,6 +82,12 @@ def parse_args():
                          "two or three steps' copies queued ahead (some 4000 hipMemcpyAsync calls) "
                          "the choice climbs to engines that move host traffic at a quarter of the "
                          "rate")
+    ap.add_argument("--pace-on", choices=["first", "parity"], default="first",
+                    help="first (default): queue a step when the first of the two copy streams has "
+                         "finished the previous one.  parity: the earlier rule, kept to show what "
+                         "it costs (wait for the previous parity snapshot, no engine re-choice): "
+                         "the second step after a start runs its two directions one after the "
+                         "other")
     ap.add_argument("--trace-phases", action="store_true",
                     help="log when each phase of each timed step began and ended (HIP events)")
     ap.add_argument("--gemm-seconds", type=float, default=0.0,
@@ -301,6 +307,9 @@ class Bench:
         b = self.ev["shard_restored"].get(n - self.args.queue_depth)
         if a is None or b is None:
             return
+        if self.args.pace_on == "parity":
+            a.synchronize()
+            return
         while not (a.query() or b.query()):
             time.sleep(100e-6)
 
@@ -311,6 +320,8 @@ class Bench:
         wait for another stream has come true (see _pace).  Step 0 has no such wait on the save
         stream, so in step 1 the save stream would still sit on the engine that the load stream,
         choosing again with everything idle, has just taken."""
+        if self.args.pace_on == "parity":
+            return
         self._wait(self.s_load, "shard_saved", n)
         self._mark("load_turn", n, self.s_load)
         self._wait(self.s_save, "load_turn", n)

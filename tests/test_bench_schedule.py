@@ -96,7 +96,7 @@ def happens_before(a, b, seen=None):
 
 def run_schedule(serial, steps):
     b = object.__new__(bench.Bench)
-    b.args = argparse.Namespace(serial=serial, queue_depth=1, trace_phases=False)
+    b.args = argparse.Namespace(serial=serial, queue_depth=1, trace_phases=False, pace_on="first")
     b.torch, b.reft = FakeTorch, FakeLib()
     b.s_save, b.s_load = FakeStream("save"), FakeStream("load")
     b.s_pack = b.s_save
