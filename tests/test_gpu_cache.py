@@ -82,6 +82,9 @@ def test_one_table_shared_by_many_streams(dev):
         for i in range(40):
             sh = [torch.full((n,), i + 1, dtype=torch.uint8, device=dev) for n in sizes]
             o = torch.empty(L, dtype=torch.uint8, device=dev)
+            # the fills run on torch's current stream: the pack's stream waits for them (and for
+            # nothing else, so the earlier readers of the retired tables may still run)
+            streams[i % 6].wait_stream(torch.cuda.current_stream())
             reft.reft_pack_device(plan, sh, o, streams[i % 6])
             others.append((sh, o, i + 1))
         torch.cuda.synchronize()

@@ -129,6 +129,7 @@ def test_noalloc_encode_replays_in_a_hip_graph(dev):
     try:
         out = torch.empty(L, dtype=torch.uint8, device=dev)
         s = torch.cuda.Stream()
+        torch.cuda.synchronize()                                    # the shards are filled
         reft.reft_parity_encode_noalloc(plan, flat, k, out, s)      # first use outside the capture
         s.synchronize()
         graph = torch.cuda.CUDAGraph()
