@@ -82,6 +82,13 @@ def parse_args():
                          "two or three steps' copies queued ahead (some 4000 hipMemcpyAsync calls) "
                          "the choice climbs to engines that move host traffic at a quarter of the "
                          "rate")
+    ap.add_argument("--settle-seconds", type=float, default=6.0,
+                    help="pause before the steps of each further configuration (--per-config): for "
+                         "a few seconds after a configuration's 100-170 GB of device memory have "
+                         "been freed, host-to-device copies run at half rate beside a device-to-"
+                         "host copy (437 instead of 222 ms for the first shard restore; with the "
+                         "pause it does not happen), presumably while the driver clears the freed "
+                         "memory")
     ap.add_argument("--pace-on", choices=["first", "parity"], default="first",
                     help="first (default): queue a step when the first of the two copy streams has "
                          "finished the previous one.  parity: the earlier rule, kept to show what "
@@ -605,6 +612,8 @@ def run_config(args, cfg, torch, reft, pinned, streams, primary):
             del x, y
         steps = args.steps if primary else args.per_config_steps
         warmup = args.warmup if primary else 1
+        if not primary:
+            time.sleep(args.settle_seconds)     # see --settle-seconds
         t_step, enc_ms, dec_ms, ok, steady = run_steps(b, steps, warmup)
         value = 4 * L / t_step / 1e9
         enc_gbps = (k + 1) * L / (enc_ms * 1e-3) / 1e9
